@@ -1,0 +1,131 @@
+/*
+ * blstm_mi355 -- one learner's training step for a bidirectional-LSTM acoustic
+ * model, and the ADPSGD pairwise weight-averaging step, as HIP kernels for gfx950.
+ *
+ * The calls follow the paper's own statement of the problem:
+ *   g  = calGrad(W)    (section 3.2)  = blstm_forward + softmax_xent_fwd_bwd + blstm_backward
+ *   W' = apply(W, g)   (section 3.2, Eq. 1c) = sgd_step
+ *   theta_i <- (theta_i' + theta_j')/2 (Eq. 4, second line) = adpsgd_mix
+ *
+ * Model (section 4.2): L bidirectional LSTM layers with H cells per direction, the
+ * two directions concatenated; a linear bottleneck of P units; a softmax over V
+ * classes; sequences unrolled over T frames with zero initial state.
+ *
+ * Conventions common to every call
+ *   - Every pointer named theta, x, z, dz, grad, labels, loss, velocity or workspace is
+ *     DEVICE memory owned by the caller.  The library never allocates or frees
+ *     device memory and never synchronises the device: all work is enqueued on the
+ *     caller's stream (a hipStream_t passed as void*, NULL = the null stream).
+ *   - `partner` and every `*_out` size/offset argument is HOST memory.
+ *   - Activations are time-major and row-major: [T][B][features].
+ *   - mode 0: every tensor is float.  mode 1: theta, x, z, dz are bfloat16 (the
+ *     bf16 shadow of the weights; RNE rounding), products accumulate in float,
+ *     gradients, the loss, the master weights and the velocity are float.
+ *   - Return value: 0 on success, otherwise one of the negative codes below; the
+ *     text is available from blstm_last_error().  Arguments are validated before
+ *     the first launch, so a call that fails validation has no side effects.
+ *   - Flat parameter layout (elements, row-major, gate blocks in the order i,f,g,o):
+ *       for layer l = 0..L-1, for direction d in (0 = forward, 1 = backward):
+ *           W_x [4H][D_l], U_h [4H][H], b [4H]      D_0 = D, D_l = 2H for l > 0
+ *       W_p [P][2H], b_p [P]                        absent when P == 0
+ *       W_s [V][P or 2H], b_s [V]
+ *     blstm_param_offset reports where each tensor sits.
+ */
+#ifndef BLSTM_MI355_H
+#define BLSTM_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BLSTM_OK              0
+#define BLSTM_ERR_NULL       -1   /* a required pointer is NULL */
+#define BLSTM_ERR_DIM        -2   /* bad dimension or unsupported configuration */
+#define BLSTM_ERR_WORKSPACE  -3   /* workspace not bound or too small */
+#define BLSTM_ERR_ALIGN      -4   /* pointer not aligned to 16 bytes */
+#define BLSTM_ERR_HIP        -5   /* a HIP call failed */
+
+/* which = one of these in blstm_param_offset */
+#define BLSTM_WX 0
+#define BLSTM_UH 1
+#define BLSTM_B  2
+#define BLSTM_WP 3
+#define BLSTM_BP 4
+#define BLSTM_WS 5
+#define BLSTM_BS 6
+
+#define BLSTM_MAX_REPLICAS 64
+
+typedef struct blstm_ctx blstm_ctx;            /* opaque, host only; owns no device memory */
+
+typedef struct {
+    int32_t T, B, D, H, L, P, V;               /* P == 0: no bottleneck, the softmax reads the LSTM output */
+    int32_t mode;                              /* 0 = fp32, 1 = bf16 storage + fp32 accumulation */
+    float   loss_scale;                        /* s of E = s * sum_frames -log p[label]; <= 0: 1/(T*B) (Eq. 1a) */
+} blstm_config;
+
+/* Context: shapes, parameter layout, workspace layout.  Host-side only. */
+int    blstm_create(const blstm_config* cfg, blstm_ctx** out);
+void   blstm_destroy(blstm_ctx* ctx);
+size_t blstm_param_count(const blstm_ctx* ctx);           /* N: elements of theta and of grad; 0 if ctx is NULL */
+size_t blstm_workspace_bytes(const blstm_ctx* ctx);       /* saved activations + scratch for one step */
+/* Offset and length (elements) of one tensor in the flat vector.  layer/dir are ignored for which >= BLSTM_WP. */
+int    blstm_param_offset(const blstm_ctx* ctx, int layer, int dir, int which, size_t* off_out, size_t* len_out);
+/* Hands the library `bytes` of caller-owned device memory (16-byte aligned) to keep between
+   blstm_forward and blstm_backward.  The contents need no initialisation. */
+int    blstm_bind(blstm_ctx* ctx, void* workspace, size_t bytes);
+
+/* Forward pass of the LSTM stack and the bottleneck (section 4.2).
+   theta [N], x [T][B][D] -> z_out [T][B][P or 2H]; activations for BPTT are kept in the workspace. */
+int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out, void* stream);
+
+/* Softmax cross-entropy over V classes (Eq. 1a with the frame-level criterion) and its gradients:
+   loss_dev[0] = s * sum -log p[label]; dz = dE/dz [T][B][P or 2H];
+   grad: only the W_s and b_s slices are written (overwritten, not accumulated).
+   labels [T][B] int32 in [0, V); out-of-range labels are not detected. */
+int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const int32_t* labels,
+                         float* loss_dev, void* dz, float* grad, void* stream);
+
+/* Back-propagation through the bottleneck and through time (Eq. 1b): writes every slice of grad
+   except W_s and b_s.  Must follow blstm_forward on the same ctx, theta and x. */
+int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void* dz, float* grad, void* stream);
+
+/* Eq. 1c: theta <- theta - lr * grad over n elements.  With momentum != 0 (velocity required):
+   v <- momentum * v + grad; theta <- theta - lr * v.  theta_bf16, if not NULL, receives the
+   RNE-rounded bf16 copy of the updated weights in the same pass. */
+int sgd_step(float* theta_master, void* theta_bf16_or_null, const float* grad, size_t n,
+             float lr, float momentum, float* velocity_or_null, void* stream);
+
+/* Eq. 4, second line, for one matching of R replicas: for every pair {i, partner[i]} both members
+   become (theta_i + theta_j)/2; partner[i] == i leaves replica i untouched.
+   theta_master: HOST array of R device pointers (n floats each); theta_bf16_or_null: HOST array of R
+   device pointers to the bf16 copies, or NULL; partner: HOST array, must be an involution. R <= 64. */
+int adpsgd_mix(float* const* theta_master, void* const* theta_bf16_or_null, size_t n, int R,
+               const int32_t* partner, void* stream);
+
+/* The alternating ring matching of section 3.2 (0-based): learners 0,2,4,.. are the senders; on even
+   steps sender i pairs with i+1, on odd steps with (i-1) mod R.  R must be even and >= 2. */
+int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
+
+/* bf16 <- RNE(master) over n elements (used once, to create the shadow of the initial weights). */
+int blstm_shadow_refresh(const float* theta_master, void* theta_bf16, size_t n, void* stream);
+
+/* Per-kernel-class timing with HIP events on the caller's stream.  enable != 0 starts recording
+   around every launch (this serialises nothing but adds event overhead); blstm_profile_read
+   synchronises the recorded events and returns, for class index k < n_classes, the summed
+   milliseconds and launch counts since the last reset.  blstm_profile_name(k) names class k. */
+int         blstm_profile_enable(blstm_ctx* ctx, int enable);
+int         blstm_profile_read(blstm_ctx* ctx, double* ms_out, int64_t* launches_out, int n_classes);
+int         blstm_profile_classes(void);
+const char* blstm_profile_name(int k);
+
+/* Text of the last error on this thread ("" if none). */
+const char* blstm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,505 @@
+// C-ABI of the library: argument validation, parameter and workspace layout, and the
+// launch order of one training step.  Host code only; every step of the path runs in the
+// kernels of gemm.hip, cell.hip, softmax.hip and update.hip.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/blstm_mi355.h"
+#include "gemm.hpp"
+#include "kernels.hpp"
+
+using namespace blstm;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline size_t up256(size_t v) { return (v + 255) & ~size_t(255); }
+
+enum ProfClass {
+    PC_GEMM_INPUT = 0, PC_GEMM_REC_FWD, PC_CELL_FWD, PC_GEMM_BOTTLENECK, PC_GEMM_LOGITS, PC_SOFTMAX_ROWS,
+    PC_GEMM_SOFTMAX_BWD, PC_GEMM_REC_BWD, PC_CELL_BWD, PC_GEMM_WGRAD, PC_GEMM_DGRAD, PC_COLSUM, PC_MISC, PC_COUNT
+};
+const char* const kProfNames[PC_COUNT] = {
+    "gemm_input_projection", "gemm_recurrent_fwd", "cell_fwd", "gemm_bottleneck", "gemm_logits", "softmax_rows",
+    "gemm_softmax_bwd", "gemm_recurrent_bwd", "cell_bwd", "gemm_wgrad", "gemm_dgrad", "colsum", "misc"};
+
+struct ProfRec { hipEvent_t a, b; int cls; };
+
+}  // namespace
+
+struct blstm_ctx {
+    blstm_config cfg;
+    int T, B, D, H, L, P, V, M, zdim;
+    DType st;                 // storage type of activations and of theta as seen by forward/backward
+    size_t esz;               // bytes per stored element
+    float s;
+    size_t nparam;
+    std::vector<size_t> off_wx[2], off_uh[2], off_b[2];
+    size_t off_wp, off_bp, off_ws, off_bs;
+    // workspace (byte offsets)
+    std::vector<size_t> wY, wG, wC;
+    size_t wAX, wPRE, wDA, wDY[2], wDH, wDC, wLOGITS, wROWLOSS, ws_bytes;
+    char* ws;
+    size_t ws_bound;
+    bool have_forward;
+    // profiling
+    bool prof;
+    std::vector<ProfRec> recs;
+    size_t recs_used;
+    double prof_ms[PC_COUNT];
+    int64_t prof_n[PC_COUNT];
+
+    int din(int l) const { return l == 0 ? D : 2 * H; }
+};
+
+namespace {
+
+struct Scope {                // records a pair of events around one launch when profiling is on
+    blstm_ctx* c; hipStream_t s; int cls; ProfRec* r;
+    Scope(blstm_ctx* c_, hipStream_t s_, int cls_) : c(c_), s(s_), cls(cls_), r(nullptr) {
+        if (!c->prof) return;
+        if (c->recs_used == c->recs.size()) {
+            ProfRec n{};
+            if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
+            c->recs.push_back(n);
+        }
+        r = &c->recs[c->recs_used++];
+        r->cls = cls;
+        (void)hipEventRecord(r->a, s);
+    }
+    ~Scope() { if (r) (void)hipEventRecord(r->b, s); }
+};
+
+int check_hip(hipError_t e, const char* what) {
+    if (e == hipSuccess) return BLSTM_OK;
+    return fail(BLSTM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define RUN(cls, what, expr)                                         \
+    do {                                                             \
+        hipError_t e_;                                               \
+        { Scope sc_(ctx, st, cls); e_ = (expr); }                    \
+        if (e_ != hipSuccess) return check_hip(e_, what);            \
+    } while (0)
+
+GemmDesc gemm_desc(DType in, DType out) {
+    GemmDesc d{};
+    d.nseg = 1; d.batch = 1; d.in_type = in; d.out_type = out;
+    return d;
+}
+
+inline const char* at(const void* base, size_t elems, size_t esz) { return static_cast<const char*>(base) + elems * esz; }
+inline char* at(void* base, size_t elems, size_t esz) { return static_cast<char*>(base) + elems * esz; }
+
+}  // namespace
+
+extern "C" {
+
+const char* blstm_last_error(void) { return g_err.c_str(); }
+
+int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
+    if (!cfg || !out) return fail(BLSTM_ERR_NULL, "blstm_create: null argument");
+    *out = nullptr;
+    if (cfg->T < 1 || cfg->B < 1 || cfg->D < 1 || cfg->H < 1 || cfg->L < 1 || cfg->P < 0 || cfg->V < 1)
+        return fail(BLSTM_ERR_DIM, "blstm_create: T,B,D,H,L,V must be >= 1 and P >= 0");
+    if (cfg->mode != 0 && cfg->mode != 1) return fail(BLSTM_ERR_DIM, "blstm_create: mode must be 0 (fp32) or 1 (bf16)");
+    const long long Mll = (long long)cfg->T * cfg->B;
+    if (Mll > (1LL << 24) || cfg->H > (1 << 14) || cfg->D > (1 << 16) || cfg->V > (1 << 22) || cfg->P > (1 << 14) || cfg->L > 64)
+        return fail(BLSTM_ERR_DIM, "blstm_create: dimension beyond the supported range");
+    blstm_ctx* c = new (std::nothrow) blstm_ctx();
+    if (!c) return fail(BLSTM_ERR_DIM, "blstm_create: out of host memory");
+    c->cfg = *cfg;
+    c->T = cfg->T; c->B = cfg->B; c->D = cfg->D; c->H = cfg->H; c->L = cfg->L; c->P = cfg->P; c->V = cfg->V;
+    c->M = (int)Mll;
+    c->zdim = cfg->P > 0 ? cfg->P : 2 * cfg->H;
+    c->st = cfg->mode == 1 ? DT_BF16 : DT_F32;
+    c->esz = cfg->mode == 1 ? 2 : 4;
+    c->s = cfg->loss_scale > 0.0f ? cfg->loss_scale : 1.0f / (float)Mll;
+    // flat parameter layout
+    size_t off = 0;
+    const size_t H = c->H;
+    for (int l = 0; l < c->L; ++l)
+        for (int d = 0; d < 2; ++d) {
+            c->off_wx[d].push_back(off); off += 4 * H * (size_t)c->din(l);
+            c->off_uh[d].push_back(off); off += 4 * H * H;
+            c->off_b[d].push_back(off);  off += 4 * H;
+        }
+    c->off_wp = off; if (c->P > 0) off += (size_t)c->P * 2 * H;
+    c->off_bp = off; if (c->P > 0) off += (size_t)c->P;
+    c->off_ws = off; off += (size_t)c->V * c->zdim;
+    c->off_bs = off; off += (size_t)c->V;
+    c->nparam = off;
+    // workspace layout
+    const size_t M = (size_t)c->M, B = (size_t)c->B, e = c->esz;
+    size_t w = 0;
+    for (int l = 0; l < c->L; ++l) {
+        c->wY.push_back(w); w += up256(M * 2 * H * e);
+        c->wG.push_back(w); w += up256(M * 8 * H * e);
+        c->wC.push_back(w); w += up256(M * 2 * H * 4);
+    }
+    c->wAX = w;      w += up256(M * 8 * H * 4);
+    c->wPRE = w;     w += up256(2 * B * 4 * H * 4);
+    c->wDA = w;      w += up256(M * 8 * H * e);
+    c->wDY[0] = w;   w += up256(M * 2 * H * e);
+    c->wDY[1] = w;   w += up256(M * 2 * H * e);
+    c->wDH = w;      w += up256(2 * B * H * 4);
+    c->wDC = w;      w += up256(2 * B * H * 4);
+    c->wLOGITS = w;  w += up256(M * (size_t)c->V * e);
+    c->wROWLOSS = w; w += up256(M * 4);
+    c->ws_bytes = w;
+    c->ws = nullptr; c->ws_bound = 0; c->have_forward = false;
+    c->prof = false; c->recs_used = 0;
+    memset(c->prof_ms, 0, sizeof c->prof_ms);
+    memset(c->prof_n, 0, sizeof c->prof_n);
+    *out = c;
+    return BLSTM_OK;
+}
+
+void blstm_destroy(blstm_ctx* c) {
+    if (!c) return;
+    for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    delete c;
+}
+
+size_t blstm_param_count(const blstm_ctx* c) { return c ? c->nparam : 0; }
+size_t blstm_workspace_bytes(const blstm_ctx* c) { return c ? c->ws_bytes : 0; }
+
+int blstm_param_offset(const blstm_ctx* c, int layer, int dir, int which, size_t* off, size_t* len) {
+    if (!c || !off || !len) return fail(BLSTM_ERR_NULL, "blstm_param_offset: null argument");
+    const size_t H = c->H;
+    if (which >= BLSTM_WX && which <= BLSTM_B) {
+        if (layer < 0 || layer >= c->L || dir < 0 || dir > 1) return fail(BLSTM_ERR_DIM, "blstm_param_offset: layer/dir out of range");
+        if (which == BLSTM_WX) { *off = c->off_wx[dir][layer]; *len = 4 * H * (size_t)c->din(layer); }
+        else if (which == BLSTM_UH) { *off = c->off_uh[dir][layer]; *len = 4 * H * H; }
+        else { *off = c->off_b[dir][layer]; *len = 4 * H; }
+        return BLSTM_OK;
+    }
+    switch (which) {
+        case BLSTM_WP: *off = c->off_wp; *len = c->P > 0 ? (size_t)c->P * 2 * H : 0; return BLSTM_OK;
+        case BLSTM_BP: *off = c->off_bp; *len = c->P > 0 ? (size_t)c->P : 0; return BLSTM_OK;
+        case BLSTM_WS: *off = c->off_ws; *len = (size_t)c->V * c->zdim; return BLSTM_OK;
+        case BLSTM_BS: *off = c->off_bs; *len = (size_t)c->V; return BLSTM_OK;
+    }
+    return fail(BLSTM_ERR_DIM, "blstm_param_offset: unknown tensor id %d", which);
+}
+
+int blstm_bind(blstm_ctx* c, void* workspace, size_t bytes) {
+    if (!c || !workspace) return fail(BLSTM_ERR_NULL, "blstm_bind: null argument");
+    if (!aligned16(workspace)) return fail(BLSTM_ERR_ALIGN, "blstm_bind: workspace must be 16-byte aligned");
+    if (bytes < c->ws_bytes) return fail(BLSTM_ERR_WORKSPACE, "blstm_bind: %zu bytes given, %zu needed", bytes, c->ws_bytes);
+    c->ws = static_cast<char*>(workspace);
+    c->ws_bound = bytes;
+    c->have_forward = false;
+    return BLSTM_OK;
+}
+
+int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out, void* stream) {
+    if (!ctx || !theta || !x || !z_out) return fail(BLSTM_ERR_NULL, "blstm_forward: null argument");
+    if (!ctx->ws) return fail(BLSTM_ERR_WORKSPACE, "blstm_forward: no workspace bound");
+    if (!aligned16(theta) || !aligned16(x) || !aligned16(z_out)) return fail(BLSTM_ERR_ALIGN, "blstm_forward: pointers must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int T = ctx->T, B = ctx->B, H = ctx->H, M = ctx->M;
+    const size_t e = ctx->esz;
+    const DType S = ctx->st;
+    float* AX = reinterpret_cast<float*>(ctx->ws + ctx->wAX);
+    float* PRE = reinterpret_cast<float*>(ctx->ws + ctx->wPRE);
+    ctx->have_forward = false;
+    for (int l = 0; l < ctx->L; ++l) {
+        const void* Xin = l == 0 ? x : static_cast<const void*>(ctx->ws + ctx->wY[l - 1]);
+        const int Din = ctx->din(l);
+        char* Y = ctx->ws + ctx->wY[l];
+        char* G = ctx->ws + ctx->wG[l];
+        float* C = reinterpret_cast<float*>(ctx->ws + ctx->wC[l]);
+        {   // a_x = W_x x + b for every frame, both directions
+            GemmDesc d = gemm_desc(S, DT_F32);
+            d.batch = 2; d.M = M; d.N = 4 * H;
+            d.seg[0] = GemmSeg{Xin, at(theta, ctx->off_wx[0][l], e), Din, Din, 0,
+                               (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]), Din};
+            d.C = AX; d.ldc = 8 * H; d.sC = 4 * H;
+            d.bias = at(theta, ctx->off_b[0][l], e); d.sBias = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);
+            RUN(PC_GEMM_INPUT, "input projection", launch_gemm(d, st));
+        }
+        for (int n = 0; n < T; ++n) {
+            const int t[2] = {n, T - 1 - n};
+            const int tp[2] = {n - 1, T - n};
+            if (n > 0) {   // a = a_x + U_h h_prev
+                GemmDesc d = gemm_desc(S, DT_F32);
+                d.batch = 2; d.M = B; d.N = 4 * H;
+                const char* A0 = Y + ((size_t)tp[0] * B * 2 * H) * e;
+                const char* A1 = Y + ((size_t)tp[1] * B * 2 * H + H) * e;
+                d.seg[0] = GemmSeg{A0, at(theta, ctx->off_uh[0][l], e), 2 * H, H, (long long)((A1 - A0) / (long long)e),
+                                   (long long)(ctx->off_uh[1][l] - ctx->off_uh[0][l]), H};
+                d.C = PRE; d.ldc = 4 * H; d.sC = (long long)B * 4 * H;
+                const float* add0 = AX + (size_t)t[0] * B * 8 * H;
+                const float* add1 = AX + (size_t)t[1] * B * 8 * H + 4 * H;
+                d.add = add0; d.ldadd = 8 * H; d.sAdd = add1 - add0;
+                RUN(PC_GEMM_REC_FWD, "recurrent product", launch_gemm(d, st));
+            }
+            CellFwdArgs a{};
+            a.B = B; a.H = H;
+            for (int dd = 0; dd < 2; ++dd) {
+                if (n > 0) { a.pre[dd] = PRE + (size_t)dd * B * 4 * H; a.ld_pre = 4 * H; }
+                else { a.pre[dd] = AX + (size_t)t[dd] * B * 8 * H + (size_t)dd * 4 * H; a.ld_pre = 8 * H; }
+                a.c_prev[dd] = n > 0 ? C + (size_t)tp[dd] * B * 2 * H + (size_t)dd * H : nullptr;
+                a.c[dd] = C + (size_t)t[dd] * B * 2 * H + (size_t)dd * H;
+                a.gates[dd] = G + ((size_t)t[dd] * B * 8 * H + (size_t)dd * 4 * H) * e;
+                a.y[dd] = Y + ((size_t)t[dd] * B * 2 * H + (size_t)dd * H) * e;
+            }
+            RUN(PC_CELL_FWD, "cell forward", launch_cell_fwd(a, S, st));
+        }
+    }
+    const char* YL = ctx->ws + ctx->wY[ctx->L - 1];
+    if (ctx->P > 0) {
+        GemmDesc d = gemm_desc(S, S);
+        d.M = M; d.N = ctx->P;
+        d.seg[0] = GemmSeg{YL, at(theta, ctx->off_wp, e), 2 * H, 2 * H, 0, 0, 2 * H};
+        d.C = z_out; d.ldc = ctx->P;
+        d.bias = at(theta, ctx->off_bp, e);
+        RUN(PC_GEMM_BOTTLENECK, "bottleneck", launch_gemm(d, st));
+    } else {
+        RUN(PC_MISC, "copy of the LSTM output", hipMemcpyAsync(z_out, YL, (size_t)M * 2 * H * e, hipMemcpyDeviceToDevice, st));
+    }
+    ctx->have_forward = true;
+    return BLSTM_OK;
+}
+
+int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const int32_t* labels,
+                         float* loss_dev, void* dz, float* grad, void* stream) {
+    if (!ctx || !theta || !z || !labels || !loss_dev || !dz || !grad) return fail(BLSTM_ERR_NULL, "softmax_xent_fwd_bwd: null argument");
+    if (!ctx->ws) return fail(BLSTM_ERR_WORKSPACE, "softmax_xent_fwd_bwd: no workspace bound");
+    if (!aligned16(theta) || !aligned16(z) || !aligned16(dz) || !aligned16(grad))
+        return fail(BLSTM_ERR_ALIGN, "softmax_xent_fwd_bwd: pointers must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int M = ctx->M, V = ctx->V, Z = ctx->zdim;
+    const size_t e = ctx->esz;
+    const DType S = ctx->st;
+    char* U = ctx->ws + ctx->wLOGITS;
+    float* row_loss = reinterpret_cast<float*>(ctx->ws + ctx->wROWLOSS);
+    {   // u = W_s z + b_s
+        GemmDesc d = gemm_desc(S, S);
+        d.M = M; d.N = V;
+        d.seg[0] = GemmSeg{z, at(theta, ctx->off_ws, e), Z, Z, 0, 0, Z};
+        d.C = U; d.ldc = V;
+        d.bias = at(theta, ctx->off_bs, e);
+        RUN(PC_GEMM_LOGITS, "logits", launch_gemm(d, st));
+    }
+    RUN(PC_SOFTMAX_ROWS, "softmax rows", launch_softmax_rows(U, V, labels, row_loss, M, V, ctx->s, S, st));
+    RUN(PC_MISC, "loss sum", launch_sum_to_scalar(row_loss, M, loss_dev, st));
+    {   // dz = du W_s
+        GemmDesc d = gemm_desc(S, S);
+        d.M = M; d.N = Z; d.btrans = true;
+        d.seg[0] = GemmSeg{U, at(theta, ctx->off_ws, e), V, Z, 0, 0, V};
+        d.C = dz; d.ldc = Z;
+        RUN(PC_GEMM_SOFTMAX_BWD, "dz", launch_gemm(d, st));
+    }
+    {   // dW_s = du^T z
+        GemmDesc d = gemm_desc(S, DT_F32);
+        d.M = V; d.N = Z; d.atrans = true; d.btrans = true;
+        d.seg[0] = GemmSeg{U, z, V, Z, 0, 0, M};
+        d.C = grad + ctx->off_ws; d.ldc = Z;
+        RUN(PC_GEMM_SOFTMAX_BWD, "dW_s", launch_gemm(d, st));
+    }
+    RUN(PC_COLSUM, "db_s", launch_colsum(U, V, M, V, grad + ctx->off_bs, nullptr, V, S, st));
+    return BLSTM_OK;
+}
+
+int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void* dz, float* grad, void* stream) {
+    if (!ctx || !theta || !x || !dz || !grad) return fail(BLSTM_ERR_NULL, "blstm_backward: null argument");
+    if (!ctx->ws) return fail(BLSTM_ERR_WORKSPACE, "blstm_backward: no workspace bound");
+    if (!ctx->have_forward) return fail(BLSTM_ERR_WORKSPACE, "blstm_backward: no forward pass is held in the workspace");
+    if (!aligned16(theta) || !aligned16(x) || !aligned16(dz) || !aligned16(grad))
+        return fail(BLSTM_ERR_ALIGN, "blstm_backward: pointers must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int T = ctx->T, B = ctx->B, H = ctx->H, M = ctx->M, P = ctx->P;
+    const size_t e = ctx->esz;
+    const DType S = ctx->st;
+    char* DA = ctx->ws + ctx->wDA;
+    float* DH = reinterpret_cast<float*>(ctx->ws + ctx->wDH);
+    float* DC = reinterpret_cast<float*>(ctx->ws + ctx->wDC);
+    const char* dY;
+    int next_buf = 0;
+    if (P > 0) {
+        const char* YL = ctx->ws + ctx->wY[ctx->L - 1];
+        {   // dW_p = dz^T y
+            GemmDesc d = gemm_desc(S, DT_F32);
+            d.M = P; d.N = 2 * H; d.atrans = true; d.btrans = true;
+            d.seg[0] = GemmSeg{dz, YL, P, 2 * H, 0, 0, M};
+            d.C = grad + ctx->off_wp; d.ldc = 2 * H;
+            RUN(PC_GEMM_WGRAD, "dW_p", launch_gemm(d, st));
+        }
+        RUN(PC_COLSUM, "db_p", launch_colsum(dz, P, M, P, grad + ctx->off_bp, nullptr, P, S, st));
+        {   // dy = dz W_p
+            GemmDesc d = gemm_desc(S, S);
+            d.M = M; d.N = 2 * H; d.btrans = true;
+            d.seg[0] = GemmSeg{dz, at(theta, ctx->off_wp, e), P, 2 * H, 0, 0, P};
+            d.C = ctx->ws + ctx->wDY[0]; d.ldc = 2 * H;
+            RUN(PC_GEMM_DGRAD, "dy of the bottleneck", launch_gemm(d, st));
+        }
+        dY = ctx->ws + ctx->wDY[0];
+        next_buf = 1;
+    } else {
+        dY = static_cast<const char*>(dz);
+    }
+    for (int l = ctx->L - 1; l >= 0; --l) {
+        const void* Xin = l == 0 ? x : static_cast<const void*>(ctx->ws + ctx->wY[l - 1]);
+        const int Din = ctx->din(l);
+        const char* Y = ctx->ws + ctx->wY[l];
+        const char* G = ctx->ws + ctx->wG[l];
+        const float* C = reinterpret_cast<const float*>(ctx->ws + ctx->wC[l]);
+        for (int n = T - 1; n >= 0; --n) {
+            const int t[2] = {n, T - 1 - n};
+            const int tp[2] = {n - 1, T - n};
+            CellBwdArgs a{};
+            a.B = B; a.H = H; a.first = (n == T - 1);
+            for (int dd = 0; dd < 2; ++dd) {
+                a.dy[dd] = dY + ((size_t)t[dd] * B * 2 * H + (size_t)dd * H) * e;
+                a.dh_rec[dd] = (n == T - 1) ? nullptr : DH + (size_t)dd * B * H;
+                a.dc_rec[dd] = DC + (size_t)dd * B * H;
+                a.gates[dd] = G + ((size_t)t[dd] * B * 8 * H + (size_t)dd * 4 * H) * e;
+                a.c[dd] = C + (size_t)t[dd] * B * 2 * H + (size_t)dd * H;
+                a.c_prev[dd] = n > 0 ? C + (size_t)tp[dd] * B * 2 * H + (size_t)dd * H : nullptr;
+                a.da[dd] = DA + ((size_t)t[dd] * B * 8 * H + (size_t)dd * 4 * H) * e;
+            }
+            RUN(PC_CELL_BWD, "cell backward", launch_cell_bwd(a, S, st));
+            if (n > 0) {   // dh_rec = da U_h
+                GemmDesc d = gemm_desc(S, DT_F32);
+                d.batch = 2; d.M = B; d.N = H; d.btrans = true;
+                const char* A0 = DA + ((size_t)t[0] * B * 8 * H) * e;
+                const char* A1 = DA + ((size_t)t[1] * B * 8 * H + 4 * H) * e;
+                d.seg[0] = GemmSeg{A0, at(theta, ctx->off_uh[0][l], e), 8 * H, H, (long long)((A1 - A0) / (long long)e),
+                                   (long long)(ctx->off_uh[1][l] - ctx->off_uh[0][l]), 4 * H};
+                d.C = DH; d.ldc = H; d.sC = (long long)B * H;
+                RUN(PC_GEMM_REC_BWD, "recurrent gradient", launch_gemm(d, st));
+            }
+        }
+        {   // dW_x = da^T x, both directions
+            GemmDesc d = gemm_desc(S, DT_F32);
+            d.batch = 2; d.M = 4 * H; d.N = Din; d.atrans = true; d.btrans = true;
+            d.seg[0] = GemmSeg{DA, Xin, 8 * H, Din, 4 * H, 0, M};
+            d.C = grad + ctx->off_wx[0][l]; d.ldc = Din; d.sC = (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]);
+            RUN(PC_GEMM_WGRAD, "dW_x", launch_gemm(d, st));
+        }
+        {   // dU_h = da^T h_prev: forward direction pairs da[t] with h[t-1], backward direction with h[t+1]
+            GemmDesc d = gemm_desc(S, DT_F32);
+            d.batch = 2; d.M = 4 * H; d.N = H; d.atrans = true; d.btrans = true;
+            const char* A0 = DA + ((size_t)B * 8 * H) * e;
+            const char* A1 = DA + ((size_t)4 * H) * e;
+            const char* B0 = Y;
+            const char* B1 = Y + ((size_t)B * 2 * H + H) * e;
+            d.seg[0] = GemmSeg{A0, B0, 8 * H, 2 * H, (long long)((A1 - A0) / (long long)e), (long long)((B1 - B0) / (long long)e), (T - 1) * B};
+            d.C = grad + ctx->off_uh[0][l]; d.ldc = H; d.sC = (long long)(ctx->off_uh[1][l] - ctx->off_uh[0][l]);
+            RUN(PC_GEMM_WGRAD, "dU_h", launch_gemm(d, st));
+        }
+        RUN(PC_COLSUM, "db", launch_colsum(DA, 8 * H, M, 8 * H, grad + ctx->off_b[0][l], grad + ctx->off_b[1][l], 4 * H, S, st));
+        if (l > 0) {   // dx = da_fwd W_x_fwd + da_bwd W_x_bwd, the gradient of the layer below's output
+            GemmDesc d = gemm_desc(S, S);
+            d.M = M; d.N = Din; d.btrans = true; d.nseg = 2;
+            d.seg[0] = GemmSeg{DA, at(theta, ctx->off_wx[0][l], e), 8 * H, Din, 0, 0, 4 * H};
+            d.seg[1] = GemmSeg{DA + (size_t)4 * H * e, at(theta, ctx->off_wx[1][l], e), 8 * H, Din, 0, 0, 4 * H};
+            d.C = ctx->ws + ctx->wDY[next_buf]; d.ldc = Din;
+            RUN(PC_GEMM_DGRAD, "dx", launch_gemm(d, st));
+            dY = ctx->ws + ctx->wDY[next_buf];
+            next_buf ^= 1;
+        }
+    }
+    return BLSTM_OK;
+}
+
+int sgd_step(float* theta, void* shadow, const float* grad, size_t n, float lr, float momentum, float* velocity, void* stream) {
+    if (!theta || !grad) return fail(BLSTM_ERR_NULL, "sgd_step: null argument");
+    if (momentum != 0.0f && !velocity) return fail(BLSTM_ERR_NULL, "sgd_step: momentum needs a velocity buffer");
+    if (!aligned16(theta) || !aligned16(grad) || (shadow && !aligned16(shadow)) || (momentum != 0.0f && !aligned16(velocity)))
+        return fail(BLSTM_ERR_ALIGN, "sgd_step: pointers must be 16-byte aligned");
+    return check_hip(launch_sgd(theta, static_cast<unsigned short*>(shadow), grad, n, lr, momentum, velocity,
+                                static_cast<hipStream_t>(stream)), "sgd_step");
+}
+
+int adpsgd_mix(float* const* theta, void* const* shadow, size_t n, int R, const int32_t* partner, void* stream) {
+    if (!theta || !partner) return fail(BLSTM_ERR_NULL, "adpsgd_mix: null argument");
+    if (R < 1 || R > BLSTM_MAX_REPLICAS) return fail(BLSTM_ERR_DIM, "adpsgd_mix: R must be in 1..%d", BLSTM_MAX_REPLICAS);
+    for (int i = 0; i < R; ++i) {
+        const int j = partner[i];
+        if (j < 0 || j >= R || partner[j] != i) return fail(BLSTM_ERR_DIM, "adpsgd_mix: partner is not an involution at %d", i);
+        if (!theta[i] || (shadow && !shadow[i])) return fail(BLSTM_ERR_NULL, "adpsgd_mix: null replica pointer %d", i);
+        if (!aligned16(theta[i]) || (shadow && !aligned16(shadow[i]))) return fail(BLSTM_ERR_ALIGN, "adpsgd_mix: replica %d is not 16-byte aligned", i);
+        for (int k = 0; k < i; ++k)
+            if (theta[k] == theta[i]) return fail(BLSTM_ERR_DIM, "adpsgd_mix: replicas %d and %d share a buffer", k, i);
+    }
+    MixPairs p{};
+    for (int i = 0; i < R; ++i) {
+        const int j = partner[i];
+        if (j <= i) continue;
+        p.a[p.npairs] = theta[i]; p.b[p.npairs] = theta[j];
+        p.sa[p.npairs] = shadow ? static_cast<unsigned short*>(shadow[i]) : nullptr;
+        p.sb[p.npairs] = shadow ? static_cast<unsigned short*>(shadow[j]) : nullptr;
+        ++p.npairs;
+    }
+    return check_hip(launch_mix(p, n, static_cast<hipStream_t>(stream)), "adpsgd_mix");
+}
+
+int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out) {
+    if (!partner_out) return fail(BLSTM_ERR_NULL, "adpsgd_ring_partner: null argument");
+    if (R < 2 || (R & 1) || step < 0) return fail(BLSTM_ERR_DIM, "adpsgd_ring_partner: R must be even and >= 2, step >= 0");
+    const bool right = (step % 2) == 0;
+    for (int i = 0; i < R; i += 2) {
+        const int j = right ? (i + 1) % R : (i + R - 1) % R;
+        partner_out[i] = j;
+        partner_out[j] = i;
+    }
+    return BLSTM_OK;
+}
+
+int blstm_shadow_refresh(const float* theta, void* shadow, size_t n, void* stream) {
+    if (!theta || !shadow) return fail(BLSTM_ERR_NULL, "blstm_shadow_refresh: null argument");
+    if (!aligned16(theta) || !aligned16(shadow)) return fail(BLSTM_ERR_ALIGN, "blstm_shadow_refresh: pointers must be 16-byte aligned");
+    return check_hip(launch_shadow(theta, static_cast<unsigned short*>(shadow), n, static_cast<hipStream_t>(stream)), "blstm_shadow_refresh");
+}
+
+int blstm_profile_classes(void) { return PC_COUNT; }
+const char* blstm_profile_name(int k) { return (k >= 0 && k < PC_COUNT) ? kProfNames[k] : ""; }
+
+int blstm_profile_enable(blstm_ctx* c, int enable) {
+    if (!c) return fail(BLSTM_ERR_NULL, "blstm_profile_enable: null argument");
+    c->prof = enable != 0;
+    c->recs_used = 0;
+    memset(c->prof_ms, 0, sizeof c->prof_ms);
+    memset(c->prof_n, 0, sizeof c->prof_n);
+    return BLSTM_OK;
+}
+
+int blstm_profile_read(blstm_ctx* c, double* ms_out, int64_t* launches_out, int n_classes) {
+    if (!c || !ms_out || !launches_out) return fail(BLSTM_ERR_NULL, "blstm_profile_read: null argument");
+    for (size_t i = 0; i < c->recs_used; ++i) {
+        ProfRec& r = c->recs[i];
+        hipError_t e = hipEventSynchronize(r.b);
+        if (e != hipSuccess) return check_hip(e, "blstm_profile_read");
+        float ms = 0.0f;
+        e = hipEventElapsedTime(&ms, r.a, r.b);
+        if (e != hipSuccess) return check_hip(e, "blstm_profile_read");
+        c->prof_ms[r.cls] += ms;
+        c->prof_n[r.cls] += 1;
+    }
+    c->recs_used = 0;
+    for (int k = 0; k < n_classes && k < PC_COUNT; ++k) { ms_out[k] = c->prof_ms[k]; launches_out[k] = c->prof_n[k]; }
+    return BLSTM_OK;
+}
+
+}  // extern "C"

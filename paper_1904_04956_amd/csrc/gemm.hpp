@@ -1,0 +1,37 @@
+// Tiled MFMA GEMM used by every dense contraction of the training step.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace blstm {
+
+enum DType { DT_F32 = 0, DT_BF16 = 1 };
+
+// One (A, B) operand pair contributing  sum_k A(m,k) * B(n,k)  to C(m,n).
+//   A(m,k) = atrans ? A[k*lda + m] : A[m*lda + k]
+//   B(n,k) = btrans ? B[k*ldb + n] : B[n*ldb + k]
+// sA/sB are element strides added per batch index (blockIdx.z); they may be negative.
+struct GemmSeg {
+    const void* A;
+    const void* B;
+    long long lda, ldb, sA, sB;
+    int K;
+};
+
+struct GemmDesc {
+    GemmSeg seg[2];
+    int nseg;                 // 1 or 2; both segments accumulate into the same C tile
+    void* C;                  // [M][N] row-major, leading dimension ldc, element type out_type
+    long long ldc, sC;
+    const void* bias;         // per column n, element type in_type, or null
+    long long sBias;
+    const float* add;         // float [M][N] added to the product, or null
+    long long ldadd, sAdd;
+    int M, N, batch;
+    bool atrans, btrans;
+    DType in_type, out_type;  // in_type is the element type of A and B
+};
+
+// Validates nothing (the caller's shapes are trusted); returns the launch status.
+hipError_t launch_gemm(const GemmDesc& d, hipStream_t stream);
+
+}  // namespace blstm

@@ -1,0 +1,117 @@
+// Streaming kernels over the flat parameter vector: SGD update (Eq. 1c), pairwise replica
+// averaging (Eq. 4, second line) and the bf16 shadow.  All are bound by HBM bandwidth:
+// every element is read once and written once with 16-byte accesses.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace blstm {
+namespace {
+
+constexpr int UPD_THREADS = 256;
+
+__device__ __forceinline__ uint2 pack4(float4 v) { return make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)); }
+
+template <bool SHADOW, bool MOM>
+__global__ __launch_bounds__(UPD_THREADS) void sgd_kernel(float* __restrict__ theta, unsigned short* __restrict__ shadow,
+                                                          const float* __restrict__ grad, float* __restrict__ vel,
+                                                          size_t n, float lr, float mu) {
+    const size_t n4 = n / 4;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 t = reinterpret_cast<const float4*>(theta)[i];
+        float4 g = reinterpret_cast<const float4*>(grad)[i];
+        if (MOM) {
+            float4 v = reinterpret_cast<const float4*>(vel)[i];
+            g.x = mu * v.x + g.x; g.y = mu * v.y + g.y; g.z = mu * v.z + g.z; g.w = mu * v.w + g.w;
+            reinterpret_cast<float4*>(vel)[i] = g;
+        }
+        t.x -= lr * g.x; t.y -= lr * g.y; t.z -= lr * g.z; t.w -= lr * g.w;
+        reinterpret_cast<float4*>(theta)[i] = t;
+        if (SHADOW) reinterpret_cast<uint2*>(shadow)[i] = pack4(t);
+    }
+    // tail (n not a multiple of four)
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const size_t i = n4 * 4 + threadIdx.x;
+        float g = grad[i];
+        if (MOM) { g = mu * vel[i] + g; vel[i] = g; }
+        const float t = theta[i] - lr * g;
+        theta[i] = t;
+        if (SHADOW) shadow[i] = f2bf(t);
+    }
+}
+
+template <bool SHADOW>
+__global__ __launch_bounds__(UPD_THREADS) void mix_kernel(MixPairs p, size_t n) {
+    const int pr = blockIdx.y;
+    float* __restrict__ a = p.a[pr];
+    float* __restrict__ b = p.b[pr];
+    const size_t n4 = n / 4;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const float4 x = reinterpret_cast<const float4*>(a)[i];
+        const float4 y = reinterpret_cast<const float4*>(b)[i];
+        float4 m;
+        m.x = 0.5f * (x.x + y.x); m.y = 0.5f * (x.y + y.y); m.z = 0.5f * (x.z + y.z); m.w = 0.5f * (x.w + y.w);
+        reinterpret_cast<float4*>(a)[i] = m;
+        reinterpret_cast<float4*>(b)[i] = m;
+        if (SHADOW) {
+            const uint2 s = pack4(m);
+            reinterpret_cast<uint2*>(p.sa[pr])[i] = s;
+            reinterpret_cast<uint2*>(p.sb[pr])[i] = s;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const size_t i = n4 * 4 + threadIdx.x;
+        const float m = 0.5f * (a[i] + b[i]);
+        a[i] = m; b[i] = m;
+        if (SHADOW) { p.sa[pr][i] = f2bf(m); p.sb[pr][i] = f2bf(m); }
+    }
+}
+
+__global__ __launch_bounds__(UPD_THREADS) void shadow_kernel(const float* __restrict__ theta, unsigned short* __restrict__ shadow, size_t n) {
+    const size_t n4 = n / 4;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
+        reinterpret_cast<uint2*>(shadow)[i] = pack4(reinterpret_cast<const float4*>(theta)[i]);
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const size_t i = n4 * 4 + threadIdx.x;
+        shadow[i] = f2bf(theta[i]);
+    }
+}
+
+unsigned blocks_for(size_t n4, unsigned cap) {
+    size_t b = (n4 + UPD_THREADS - 1) / UPD_THREADS;
+    if (b < 1) b = 1;
+    return (unsigned)(b < cap ? b : cap);
+}
+
+}  // namespace
+
+hipError_t launch_sgd(float* theta, unsigned short* shadow, const float* grad, size_t n, float lr, float mu,
+                      float* vel, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    dim3 grid(blocks_for(n / 4, 256 * 16)), block(UPD_THREADS);
+    const bool mom = (mu != 0.0f);
+    if (shadow && mom) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, block, 0, st, theta, shadow, grad, vel, n, lr, mu);
+    else if (shadow) hipLaunchKernelGGL((sgd_kernel<true, false>), grid, block, 0, st, theta, shadow, grad, vel, n, lr, mu);
+    else if (mom) hipLaunchKernelGGL((sgd_kernel<false, true>), grid, block, 0, st, theta, shadow, grad, vel, n, lr, mu);
+    else hipLaunchKernelGGL((sgd_kernel<false, false>), grid, block, 0, st, theta, shadow, grad, vel, n, lr, mu);
+    return hipGetLastError();
+}
+
+hipError_t launch_mix(const MixPairs& p, size_t n, hipStream_t st) {
+    if (n == 0 || p.npairs == 0) return hipSuccess;
+    unsigned per_pair = blocks_for(n / 4, (256 * 16 + p.npairs - 1) / p.npairs);
+    dim3 grid(per_pair, (unsigned)p.npairs), block(UPD_THREADS);
+    if (p.sa[0]) hipLaunchKernelGGL(mix_kernel<true>, grid, block, 0, st, p, n);
+    else hipLaunchKernelGGL(mix_kernel<false>, grid, block, 0, st, p, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_shadow(const float* theta, unsigned short* shadow, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(shadow_kernel, dim3(blocks_for(n / 4, 256 * 16)), dim3(UPD_THREADS), 0, st, theta, shadow, n);
+    return hipGetLastError();
+}
+
+}  // namespace blstm

@@ -1,0 +1,114 @@
+"""Device-memory plumbing around the C-ABI calls: one learner's buffers and step order.
+
+PyTorch allocates the buffers and provides the stream; every computation is a call
+into the library through `binding`.  Used by the GPU tests, the smoke check and the
+benchmark.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as bl
+from . import inputs
+
+
+class Learner:
+    """Buffers of one learner: master weights, bf16 shadow, gradient, batch, workspace."""
+
+    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("a GPU is required: the HIP path has no CPU fallback")
+        self.dims = dict(T=T, B=B, D=D, H=H, L=L, P=P, V=V)
+        self.mode = mode
+        self.device = torch.device(device)
+        self.ctx = bl.blstm_create(T, B, D, H, L, P, V, mode, loss_scale)
+        self.n = bl.blstm_param_count(self.ctx)
+        self.zdim = P if P > 0 else 2 * H
+        self.act_dtype = torch.bfloat16 if mode == 1 else torch.float32
+        dev = self.device
+        self.workspace = torch.empty(bl.blstm_workspace_bytes(self.ctx), dtype=torch.uint8, device=dev)
+        bl.blstm_bind(self.ctx, self.workspace)
+        self.theta = torch.zeros(self.n, dtype=torch.float32, device=dev)
+        self.shadow = torch.zeros(self.n, dtype=torch.bfloat16, device=dev) if mode == 1 else None
+        self.grad = torch.zeros(self.n, dtype=torch.float32, device=dev)
+        self.velocity = torch.zeros(self.n, dtype=torch.float32, device=dev) if momentum != 0.0 else None
+        self.momentum = momentum
+        self.x = torch.zeros((T, B, D), dtype=self.act_dtype, device=dev)
+        self.labels = torch.zeros((T, B), dtype=torch.int32, device=dev)
+        self.z = torch.zeros((T, B, self.zdim), dtype=self.act_dtype, device=dev)
+        self.dz = torch.zeros((T, B, self.zdim), dtype=self.act_dtype, device=dev)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    def close(self):
+        if self.ctx is not None:
+            bl.blstm_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- data in ---------------------------------------------------------------------
+    def set_theta(self, theta_f32: np.ndarray):
+        assert theta_f32.dtype == np.float32 and theta_f32.size == self.n
+        self.theta.copy_(torch.from_numpy(theta_f32))
+        if self.shadow is not None:
+            bl.blstm_shadow_refresh(self.theta, self.shadow, self.n)
+
+    def set_batch(self, x_f32: np.ndarray, labels_i32: np.ndarray):
+        self.x.copy_(torch.from_numpy(x_f32).to(self.act_dtype))
+        self.labels.copy_(torch.from_numpy(labels_i32.astype(np.int32)))
+
+    @property
+    def theta_fwd(self):
+        """The weights as the forward and backward passes read them."""
+        return self.shadow if self.mode == 1 else self.theta
+
+    # ---- the step ----------------------------------------------------------------------
+    def forward(self, stream=None):
+        bl.blstm_forward(self.ctx, self.theta_fwd, self.x, self.z, stream)
+
+    def calgrad(self, stream=None):
+        """g = calGrad(W): forward, softmax cross-entropy, backward."""
+        th = self.theta_fwd
+        bl.blstm_forward(self.ctx, th, self.x, self.z, stream)
+        bl.softmax_xent_fwd_bwd(self.ctx, th, self.z, self.labels, self.loss, self.dz, self.grad, stream)
+        bl.blstm_backward(self.ctx, th, self.x, self.dz, self.grad, stream)
+
+    def apply(self, lr, stream=None):
+        """W' = apply(W, g)."""
+        bl.sgd_step(self.theta, self.shadow, self.grad, self.n, lr, self.momentum, self.velocity, stream)
+
+    def train_step(self, lr, stream=None):
+        self.calgrad(stream)
+        self.apply(lr, stream)
+
+    # ---- data out --------------------------------------------------------------------
+    def loss_value(self) -> float:
+        return float(self.loss.cpu()[0])
+
+    def grad_numpy(self) -> np.ndarray:
+        return self.grad.cpu().numpy()
+
+    def theta_numpy(self) -> np.ndarray:
+        return self.theta.cpu().numpy()
+
+    def z_numpy(self) -> np.ndarray:
+        return self.z.float().cpu().numpy()
+
+
+def learner_for(workload: inputs.Workload, B=None, device="cuda:0", momentum=0.0) -> Learner:
+    d = workload.dims()
+    if B is not None:
+        d["B"] = B
+    return Learner(mode=workload.mode, device=device, momentum=momentum, **d)
+
+
+def mix(learners, partner, stream=None):
+    """One ADPSGD averaging step over the learners' weights (and their bf16 shadows)."""
+    masters = [l.theta for l in learners]
+    shadows = [l.shadow for l in learners] if learners[0].shadow is not None else None
+    bl.adpsgd_mix(masters, shadows, learners[0].n, len(learners), partner, stream)

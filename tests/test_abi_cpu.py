@@ -1,0 +1,135 @@
+"""The C-ABI library loads, exports what include/blstm_mi355.h declares, and its host-side
+logic (validation, layouts, the ring schedule) behaves; no kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import blstm_oracle as orc
+from paper_1904_04956_amd import binding as bl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "blstm_mi355.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", " ".join(l for l in text.splitlines() if not l.startswith("#")))))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"blstm_forward", "blstm_backward", "softmax_xent_fwd_bwd", "sgd_step", "adpsgd_mix"} <= set(names)
+    L = bl.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(bl.EXPORTS) == names
+
+
+def test_param_count_and_offsets_match_the_closed_form():
+    # the paper's own model: 43 130 368 parameters (165 MB in float)
+    ctx = bl.blstm_create(21, 256, 260, 512, 6, 256, 32000, 1)
+    try:
+        assert bl.blstm_param_count(ctx) == 43_130_368
+        assert bl.blstm_workspace_bytes(ctx) > 0
+    finally:
+        bl.blstm_destroy(ctx)
+    for shape in (dict(T=3, B=2, D=5, H=4, L=2, P=3, V=7), dict(T=21, B=8, D=40, H=32, L=1, P=0, V=100),
+                  dict(T=21, B=256, D=260, H=512, L=4, P=256, V=32000)):
+        ctx = bl.blstm_create(mode=0, **shape)
+        try:
+            dm = orc.Dims(**shape)
+            assert bl.blstm_param_count(ctx) == orc.param_count(dm)
+            lay = {n: (o, int(np.prod(s))) for n, o, s in orc.layout(dm)}
+            for l in range(dm.L):
+                for d in range(2):
+                    assert bl.blstm_param_offset(ctx, l, d, bl.BLSTM_WX) == lay[f"Wx{l}.{d}"]
+                    assert bl.blstm_param_offset(ctx, l, d, bl.BLSTM_UH) == lay[f"Uh{l}.{d}"]
+                    assert bl.blstm_param_offset(ctx, l, d, bl.BLSTM_B) == lay[f"b{l}.{d}"]
+            if dm.P > 0:
+                assert bl.blstm_param_offset(ctx, 0, 0, bl.BLSTM_WP) == lay["Wp"]
+                assert bl.blstm_param_offset(ctx, 0, 0, bl.BLSTM_BP) == lay["bp"]
+            else:
+                assert bl.blstm_param_offset(ctx, 0, 0, bl.BLSTM_WP)[1] == 0
+            assert bl.blstm_param_offset(ctx, 0, 0, bl.BLSTM_WS) == lay["Ws"]
+            assert bl.blstm_param_offset(ctx, 0, 0, bl.BLSTM_BS) == lay["bs"]
+        finally:
+            bl.blstm_destroy(ctx)
+
+
+def test_create_rejects_bad_dimensions():
+    for bad in (dict(T=0), dict(B=0), dict(H=-1), dict(V=0), dict(P=-1), dict(mode=2), dict(L=0)):
+        kw = dict(T=2, B=2, D=2, H=2, L=1, P=0, V=2, mode=0)
+        kw.update(bad)
+        with pytest.raises(bl.BlstmError) as e:
+            bl.blstm_create(**kw)
+        assert e.value.code == -2
+    L = bl.lib()
+    assert L.blstm_create(None, None) == -1
+    assert L.blstm_param_count(None) == 0
+    L.blstm_destroy(None)
+
+
+def test_calls_validate_before_launching():
+    ctx = bl.blstm_create(2, 2, 2, 2, 1, 0, 2, 0)
+    L = bl.lib()
+    try:
+        assert L.blstm_forward(ctx, None, None, None, None) == -1
+        # valid-looking (never dereferenced) addresses, but no workspace bound
+        assert L.blstm_forward(ctx, 4096, 4096, 4096, None) == -3
+        assert "workspace" in bl.blstm_last_error()
+        assert L.blstm_backward(ctx, 4096, 4096, 4096, 4096, None) == -3
+        assert L.softmax_xent_fwd_bwd(ctx, 4096, 4096, 4096, 4096, 4096, 4096, None) == -3
+        assert L.blstm_bind(ctx, 4096, 1) == -3
+        assert L.blstm_bind(ctx, 4100, 1 << 30) == -4
+        assert L.blstm_bind(ctx, 4096, 1 << 30) == 0
+        assert L.blstm_forward(ctx, 4100, 4096, 4096, None) == -4
+        assert L.blstm_backward(ctx, 4096, 4096, 4096, 4096, None) == -3      # no forward pass held
+        assert L.sgd_step(None, None, None, 0, 0.1, 0.0, None, None) == -1
+        assert L.sgd_step(4096, None, 4096, 8, 0.1, 0.9, None, None) == -1    # momentum without velocity
+        assert L.sgd_step(4100, None, 4096, 8, 0.1, 0.0, None, None) == -4
+        assert L.blstm_shadow_refresh(None, None, 0, None) == -1
+        with pytest.raises(bl.BlstmError):
+            bl.blstm_param_offset(ctx, 5, 0, bl.BLSTM_WX)
+        with pytest.raises(bl.BlstmError):
+            bl.blstm_param_offset(ctx, 0, 0, 99)
+    finally:
+        bl.blstm_destroy(ctx)
+
+
+def test_mix_validation():
+    L = bl.lib()
+    ptrs = (ctypes.c_void_p * 4)(4096, 8192, 12288, 16384)
+    ok = (ctypes.c_int32 * 4)(1, 0, 3, 2)
+    bad = (ctypes.c_int32 * 4)(1, 2, 3, 0)
+    assert L.adpsgd_mix(None, None, 16, 4, ok, None) == -1
+    assert L.adpsgd_mix(ptrs, None, 16, 0, ok, None) == -2
+    assert L.adpsgd_mix(ptrs, None, 16, 65, ok, None) == -2
+    assert L.adpsgd_mix(ptrs, None, 16, 4, bad, None) == -2
+    assert "involution" in bl.blstm_last_error()
+    same = (ctypes.c_void_p * 4)(4096, 8192, 4096, 16384)
+    assert L.adpsgd_mix(same, None, 16, 4, ok, None) == -2
+    odd = (ctypes.c_void_p * 4)(4096, 8196, 12288, 16384)
+    assert L.adpsgd_mix(odd, None, 16, 4, ok, None) == -4
+    # nothing to do: n == 0 launches nothing and succeeds
+    assert L.adpsgd_mix(ptrs, None, 0, 4, ok, None) == 0
+
+
+def test_ring_partner_matches_the_oracle_schedule():
+    for R in (2, 4, 16, 64):
+        for step in range(5):
+            assert bl.adpsgd_ring_partner(R, step) == orc.adpsgd_ring_partner(R, step)
+    for R, step in ((0, 0), (5, 0), (4, -1)):
+        with pytest.raises(bl.BlstmError):
+            bl.adpsgd_ring_partner(R, step)
+
+
+def test_profile_names():
+    L = bl.lib()
+    k = L.blstm_profile_classes()
+    names = [L.blstm_profile_name(i).decode() for i in range(k)]
+    assert len(set(names)) == k and all(names)
+    assert L.blstm_profile_name(k) == b""

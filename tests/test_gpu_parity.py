@@ -1,0 +1,278 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the float64 oracle on the same
+seeded inputs.
+
+Error measure (stated with every number): per tensor, max|gpu - ref| / max|ref|.
+Tolerances: fp32 mode 1e-4, bf16 mode 2e-2 on the loss, every gradient tensor and the
+updated weights.  In bf16 mode the oracle is fed the bf16-rounded weights and features, so the
+budget measures the arithmetic, not the input quantisation.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import blstm_oracle as orc
+from paper_1904_04956_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = {0: 1e-4, 1: 2e-2}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def rel_err(a, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.abs(ref).max()
+    num = np.abs(np.asarray(a, dtype=np.float64) - ref).max()
+    return num / den if den > 0 else num
+
+
+def make_problem(dims, mode, seed, theta_scale=1.0):
+    dm = orc.Dims(**dims)
+    n = orc.param_count(dm)
+    bf = mode == 1
+    theta = inputs.make_theta(n, seed, bf16=False) * np.float32(theta_scale)
+    if bf:
+        theta = inputs.round_to_bf16(theta)
+    x, labels = inputs.make_batch(dm.T, dm.B, dm.D, dm.V, seed, bf16=bf)
+    return dm, theta, x, labels
+
+
+def check_step(dims, mode, seed, lr=0.1, theta_scale=1.0, tol=None, check_update=True):
+    """One full training step on the GPU against the oracle; returns the worst relative error."""
+    from paper_1904_04956_amd.harness import Learner
+    tol = TOL[mode] if tol is None else tol
+    dm, theta, x, labels = make_problem(dims, mode, seed, theta_scale)
+    say(f"case dims={dims} mode={mode} seed={seed}")
+    lrn = Learner(mode=mode, **dims)
+    try:
+        lrn.set_theta(theta)
+        lrn.set_batch(x, labels)
+        lrn.calgrad()
+        z_gpu = lrn.z_numpy()
+        loss_gpu = lrn.loss_value()
+        g_gpu = lrn.grad_numpy()
+        lrn.apply(lr)
+        th_gpu = lrn.theta_numpy()
+        sh_gpu = lrn.shadow.float().cpu().numpy() if mode == 1 else None
+    finally:
+        lrn.close()
+    th64 = theta.astype(np.float64)
+    z_ref, _ = orc.blstm_forward(dm, th64, x)
+    loss_ref, g_ref = orc.loss_and_grad(dm, th64, x, labels)
+    worst = 0.0
+    e = rel_err(z_gpu, z_ref); worst = max(worst, e)
+    assert e <= tol, f"z: {e}"
+    e = abs(loss_gpu - loss_ref) / abs(loss_ref); worst = max(worst, e)
+    assert e <= tol, f"loss: gpu {loss_gpu} ref {loss_ref}"
+    assert np.all(np.isfinite(g_gpu))
+    for name, off, shape in orc.layout(dm):
+        k = int(np.prod(shape))
+        e = rel_err(g_gpu[off:off + k], g_ref[off:off + k]); worst = max(worst, e)
+        assert e <= tol, f"grad {name}: {e}"
+    if check_update:
+        # the update itself is exact arithmetic on the GPU's own gradient: check it tightly ...
+        th_exact = theta.astype(np.float64) - lr * g_gpu.astype(np.float64)
+        assert rel_err(th_gpu, th_exact) <= 1e-6
+        # ... and the updated weights against the oracle's step within the mode's tolerance
+        th_ref, _ = orc.sgd_step(th64, g_ref, lr)
+        for name, off, shape in orc.layout(dm):
+            k = int(np.prod(shape))
+            e = rel_err(th_gpu[off:off + k], th_ref[off:off + k]); worst = max(worst, e)
+            assert e <= tol, f"theta {name}: {e}"
+        if sh_gpu is not None:
+            assert np.array_equal(sh_gpu, inputs.round_to_bf16(th_gpu))
+    say(f"  worst relative error {worst:.3e} (tolerance {tol:g})")
+    return worst
+
+
+# ------------------------------------------------------------------ fp32 mode
+
+def test_tiny_workload_fp32():
+    w = inputs.WORKLOADS["tiny"]
+    check_step(w.dims(), 0, w.seed, lr=w.lr)
+
+
+@pytest.mark.parametrize("dims", [
+    dict(T=1, B=1, D=1, H=1, L=1, P=0, V=2),                # smallest possible
+    dict(T=2, B=3, D=5, H=4, L=2, P=3, V=7),                # odd everything: scalar load paths
+    dict(T=5, B=37, D=40, H=32, L=2, P=24, V=100),          # M = 185: two row tiles with a ragged tail
+    dict(T=3, B=130, D=36, H=96, L=2, P=0, V=300),          # 4H = 384, V = 300: several column tiles, no bottleneck
+    dict(T=1, B=16, D=12, H=8, L=1, P=4, V=10),             # a single frame: no recurrent product at all
+])
+def test_odd_shapes_fp32(dims):
+    check_step(dims, 0, seed=77, theta_scale=3.0)
+
+
+def test_loss_scale_argument_fp32():
+    from paper_1904_04956_amd.harness import Learner
+    dims = dict(T=4, B=6, D=8, H=8, L=1, P=0, V=9)
+    dm, theta, x, labels = make_problem(dims, 0, 5)
+    lrn = Learner(mode=0, loss_scale=1.0 / 6, **dims)
+    try:
+        lrn.set_theta(theta); lrn.set_batch(x, labels); lrn.calgrad()
+        loss, g = lrn.loss_value(), lrn.grad_numpy()
+    finally:
+        lrn.close()
+    dmb = orc.Dims(loss_scale=1.0 / 6, **dims)
+    lref, gref = orc.loss_and_grad(dmb, theta.astype(np.float64), x, labels)
+    assert abs(loss - lref) <= 1e-4 * abs(lref)
+    assert rel_err(g, gref) <= 1e-4
+
+
+# ------------------------------------------------------------------ bf16 mode
+
+@pytest.mark.parametrize("dims", [
+    dict(T=21, B=32, D=260, H=128, L=2, P=64, V=1000),      # the paper's feature width, K tail 260 = 4*64 + 4
+    dict(T=4, B=19, D=20, H=24, L=2, P=12, V=50),           # nothing a multiple of a tile
+    dict(T=3, B=5, D=7, H=6, L=1, P=0, V=11),               # odd leading dimensions: scalar load paths
+])
+def test_shapes_bf16(dims):
+    check_step(dims, 1, seed=78, theta_scale=2.0)
+
+
+def test_paper_shaped_workload_bf16_full_size():
+    # the configuration the benchmark times, compared in full
+    w = inputs.WORKLOADS["paper4x512"]
+    check_step(w.dims(), 1, w.seed, lr=w.lr)
+
+
+def test_paper_shaped_workload_fp32_mode_reduced_batch():
+    # same model in fp32 mode for the 1e-4 bar (a quarter of the batch keeps the oracle short)
+    w = inputs.WORKLOADS["paper4x512"]
+    d = w.dims(); d["B"] = 64
+    check_step(d, 0, w.seed, lr=w.lr)
+
+
+# ------------------------------------------------------------------ update kernels
+
+@pytest.mark.parametrize("n", [1, 3, 4, 1000, 1027, 4099, 1 << 20])
+@pytest.mark.parametrize("momentum", [0.0, 0.9])
+def test_sgd_step_against_oracle(n, momentum):
+    import torch
+    from paper_1904_04956_amd import binding as bl
+    rng = np.random.default_rng(n)
+    th = rng.standard_normal(n).astype(np.float32)
+    g = rng.standard_normal(n).astype(np.float32)
+    v = rng.standard_normal(n).astype(np.float32)
+    dth, dg, dv = (torch.from_numpy(a).cuda() for a in (th, g, v))
+    dsh = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    bl.sgd_step(dth, dsh, dg, n, 0.05, momentum, dv if momentum else None)
+    ref_t, ref_v = orc.sgd_step(th, g, 0.05, momentum, v)
+    out = dth.cpu().numpy()
+    assert np.abs(out - ref_t).max() <= 2e-7 * max(1.0, np.abs(ref_t).max())
+    if momentum:
+        assert np.abs(dv.cpu().numpy() - ref_v).max() <= 2e-7 * np.abs(ref_v).max()
+    else:
+        assert np.array_equal(dv.cpu().numpy(), v)
+    assert np.array_equal(dsh.float().cpu().numpy(), inputs.round_to_bf16(out))
+    # lr = 0 is the identity
+    before = dth.clone()
+    bl.sgd_step(dth, None, dg, n, 0.0, 0.0, None)
+    assert torch.equal(before, dth)
+
+
+@pytest.mark.parametrize("n,R", [(5, 2), (1027, 4), (1 << 18, 16)])
+def test_adpsgd_mix_against_oracle(n, R):
+    import torch
+    from paper_1904_04956_amd import binding as bl
+    rng = np.random.default_rng(R)
+    th = [rng.standard_normal(n).astype(np.float32) for _ in range(R)]
+    dth = [torch.from_numpy(a).cuda() for a in th]
+    dsh = [torch.zeros(n, dtype=torch.bfloat16, device="cuda") for _ in range(R)]
+    ref = [a.astype(np.float64) for a in th]
+    for step in range(6):
+        partner = bl.adpsgd_ring_partner(R, step)
+        bl.adpsgd_mix(dth, dsh, n, R, partner)
+        ref = orc.adpsgd_mix(ref, partner)
+        out = [d.cpu().numpy() for d in dth]
+        for i in range(R):
+            assert np.array_equal(out[i], out[partner[i]])                       # pair members bit-equal
+            assert np.abs(out[i] - ref[i]).max() <= 1e-6 * np.abs(ref[i]).max()
+            assert np.array_equal(dsh[i].float().cpu().numpy(), inputs.round_to_bf16(out[i]))
+    mean0 = np.mean(np.stack([a.astype(np.float64) for a in th]), axis=0)
+    mean1 = np.mean(np.stack([d.cpu().numpy().astype(np.float64) for d in dth]), axis=0)
+    assert np.abs(mean1 - mean0).max() <= 1e-6 * np.abs(mean0).max()
+    # a learner paired with itself is left untouched
+    partner = list(range(R))
+    snap = [d.clone() for d in dth]
+    bl.adpsgd_mix(dth, None, n, R, partner)
+    assert all(torch.equal(a, b) for a, b in zip(snap, dth))
+
+
+def test_adpsgd_mix_full_size_mean_invariant():
+    # sixteen replicas of the paper-shaped model resident in HBM, as in the ADPSGD workload
+    import torch
+    from paper_1904_04956_amd import binding as bl
+    n, R = 30_539_264, 16
+    gen = torch.Generator(device="cuda").manual_seed(4956)
+    dth = [torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-0.1, 0.1, generator=gen) for _ in range(R)]
+    dsh = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(R)]
+    mean0 = torch.stack([d.double() for d in dth]).mean(dim=0)
+    before = [d.cpu().numpy() for d in dth[:4]]
+    for step in range(2):
+        partner = bl.adpsgd_ring_partner(R, step)
+        bl.adpsgd_mix(dth, dsh, n, R, partner)
+        if step == 0:
+            ref = orc.adpsgd_mix(before[:2], [1, 0])
+            assert np.abs(dth[0].cpu().numpy() - ref[0]).max() <= 1e-7
+            assert torch.equal(dth[0], dth[1]) and torch.equal(dth[2], dth[3])
+    mean1 = torch.stack([d.double() for d in dth]).mean(dim=0)
+    err = float((mean1 - mean0).abs().max() / mean0.abs().max())
+    say(f"replica mean after two mixing steps: relative error {err:.2e}")
+    assert err <= 1e-6
+    assert torch.equal(dsh[5].float(), dth[5].bfloat16().float())
+
+
+# ------------------------------------------------------------------ reproducibility, ADPSGD end to end
+
+def test_run_to_run_bit_reproducible():
+    from paper_1904_04956_amd.harness import Learner
+    dims = dict(T=6, B=40, D=36, H=64, L=2, P=32, V=500)
+    dm, theta, x, labels = make_problem(dims, 1, 3)
+    outs = []
+    for _ in range(3):
+        lrn = Learner(mode=1, **dims)
+        lrn.set_theta(theta); lrn.set_batch(x, labels); lrn.calgrad()
+        outs.append((lrn.loss_value(), lrn.grad_numpy().copy()))
+        lrn.close()
+    for l, g in outs[1:]:
+        assert l == outs[0][0] and np.array_equal(g, outs[0][1])
+
+
+def test_adpsgd_iterations_reduced_width():
+    """Sixteen learners, ten iterations of local step + ring averaging (the ADPSGD workload with the
+    model narrowed to H = 64, V = 1000 so that the oracle runs all of it)."""
+    from paper_1904_04956_amd import binding as bl
+    from paper_1904_04956_amd.harness import Learner, mix
+    dims = dict(T=21, B=8, D=260, H=64, L=2, P=32, V=1000)
+    R, iters, lr, mode = 16, 10, 0.05, 0
+    dm = orc.Dims(**dims)
+    n = orc.param_count(dm)
+    theta0 = inputs.make_theta(n, 4956)
+    learners = [Learner(mode=mode, **dims) for _ in range(R)]
+    for l in learners:
+        l.set_theta(theta0)
+    ref = [theta0.astype(np.float64) for _ in range(R)]
+    for it in range(iters):
+        for r, l in enumerate(learners):
+            x, labels = inputs.make_batch(dm.T, dm.B, dm.D, dm.V, 5000 + 16 * it + r)
+            l.set_batch(x, labels)
+            l.train_step(lr)
+            _, g = orc.loss_and_grad(dm, ref[r], x, labels)
+            ref[r], _ = orc.sgd_step(ref[r], g, lr)
+        partner = bl.adpsgd_ring_partner(R, it)
+        mean_before = np.mean([l.theta_numpy().astype(np.float64) for l in learners], axis=0)
+        mix(learners, partner)
+        mean_after = np.mean([l.theta_numpy().astype(np.float64) for l in learners], axis=0)
+        assert np.abs(mean_after - mean_before).max() <= 1e-6 * np.abs(mean_before).max()
+        ref = orc.adpsgd_mix(ref, partner)
+    worst = max(rel_err(l.theta_numpy(), ref[r]) for r, l in enumerate(learners))
+    say(f"ADPSGD, {iters} iterations, {R} learners: worst relative error of the weights {worst:.2e}")
+    assert worst <= 1e-4
+    for l in learners:
+        l.close()
