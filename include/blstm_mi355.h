@@ -110,6 +110,17 @@ int adpsgd_mix(float* const* theta_master, void* const* theta_bf16_or_null, size
    steps sender i pairs with i+1, on odd steps with (i-1) mod R.  R must be even and >= 2. */
 int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
 
+/* Options.  BLSTM_OPT_RECURRENT_PATH: 0 (default) runs each layer's T recurrent frames in one
+   persistent kernel where the shape allows it (mode 1, H a multiple of 128 up to 512, grid
+   co-resident on the device), 1 forces one launch per frame everywhere. */
+#define BLSTM_OPT_RECURRENT_PATH 1
+int blstm_set_option(blstm_ctx* ctx, int option, int value);
+
+/* The only call that synchronises: waits for `stream`, then reports whether a persistent kernel
+   gave up a wait on another workgroup (BLSTM_ERR_HIP; the results of that step are invalid).
+   Returns 0 otherwise. */
+int blstm_device_status(blstm_ctx* ctx, void* stream);
+
 /* bf16 <- RNE(master) over n elements (used once, to create the shadow of the initial weights). */
 int blstm_shadow_refresh(const float* theta_master, void* theta_bf16, size_t n, void* stream);
 

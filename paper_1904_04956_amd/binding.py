@@ -20,7 +20,7 @@ BLSTM_MAX_REPLICAS = 64
 EXPORTS = [
     "blstm_create", "blstm_destroy", "blstm_param_count", "blstm_workspace_bytes", "blstm_param_offset",
     "blstm_bind", "blstm_forward", "softmax_xent_fwd_bwd", "blstm_backward", "sgd_step", "adpsgd_mix",
-    "adpsgd_ring_partner", "blstm_shadow_refresh", "blstm_profile_enable", "blstm_profile_read",
+    "adpsgd_ring_partner", "blstm_shadow_refresh", "blstm_set_option", "blstm_device_status", "blstm_profile_enable", "blstm_profile_read",
     "blstm_profile_classes", "blstm_profile_name", "blstm_last_error",
 ]
 
@@ -73,6 +73,10 @@ def lib():
     L.adpsgd_ring_partner.restype = c_int
     L.blstm_shadow_refresh.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     L.blstm_shadow_refresh.restype = c_int
+    L.blstm_set_option.argtypes = [c_void_p, c_int, c_int]
+    L.blstm_set_option.restype = c_int
+    L.blstm_device_status.argtypes = [c_void_p, c_void_p]
+    L.blstm_device_status.restype = c_int
     L.blstm_profile_enable.argtypes = [c_void_p, c_int]
     L.blstm_profile_enable.restype = c_int
     L.blstm_profile_read.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int64), c_int]
@@ -182,6 +186,17 @@ def adpsgd_ring_partner(R, step):
 
 def blstm_shadow_refresh(theta_master, theta_bf16, n, stream=None):
     return _check(lib().blstm_shadow_refresh(_ptr(theta_master), _ptr(theta_bf16), n, _stream(stream)))
+
+
+BLSTM_OPT_RECURRENT_PATH = 1
+
+
+def blstm_set_option(ctx, option, value):
+    return _check(lib().blstm_set_option(ctx, option, value))
+
+
+def blstm_device_status(ctx, stream=None):
+    return _check(lib().blstm_device_status(ctx, _stream(stream)))
 
 
 # --------------------------------------------------------------------------- per-kernel-class timing

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libblstm_mi355.so")
-SOURCES = ["api.hip", "gemm.hip", "cell.hip", "softmax.hip", "update.hip"]
+SOURCES = ["api.hip", "gemm.hip", "recurrent.hip", "cell.hip", "softmax.hip", "update.hip"]
 
 # The packed-fp32 feature is switched off for all device code on purpose.
 HIPCC_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -35,11 +35,13 @@ inline size_t up256(size_t v) { return (v + 255) & ~size_t(255); }
 
 enum ProfClass {
     PC_GEMM_INPUT = 0, PC_GEMM_REC_FWD, PC_CELL_FWD, PC_GEMM_BOTTLENECK, PC_GEMM_LOGITS, PC_SOFTMAX_ROWS,
-    PC_GEMM_SOFTMAX_BWD, PC_GEMM_REC_BWD, PC_CELL_BWD, PC_GEMM_WGRAD, PC_GEMM_DGRAD, PC_COLSUM, PC_MISC, PC_COUNT
+    PC_GEMM_SOFTMAX_BWD, PC_GEMM_REC_BWD, PC_CELL_BWD, PC_GEMM_WGRAD, PC_GEMM_DGRAD, PC_MISC,
+    PC_REC_FWD, PC_REC_BWD, PC_COUNT
 };
 const char* const kProfNames[PC_COUNT] = {
     "gemm_input_projection", "gemm_recurrent_fwd", "cell_fwd", "gemm_bottleneck", "gemm_logits", "softmax_rows",
-    "gemm_softmax_bwd", "gemm_recurrent_bwd", "cell_bwd", "gemm_wgrad", "gemm_dgrad", "colsum", "misc"};
+    "gemm_softmax_bwd", "gemm_recurrent_bwd", "cell_bwd", "gemm_wgrad", "gemm_dgrad", "misc",
+    "recurrent_fwd_persistent", "recurrent_bwd_persistent"};
 
 struct ProfRec { hipEvent_t a, b; int cls; };
 
@@ -56,7 +58,10 @@ struct blstm_ctx {
     size_t off_wp, off_bp, off_ws, off_bs;
     // workspace (byte offsets)
     std::vector<size_t> wY, wG, wC;
-    size_t wAX, wPRE, wDA, wDY[2], wDH, wDC, wLOGITS, wROWLOSS, ws_bytes;
+    size_t wAX, wPRE, wDA, wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, ws_bytes;
+    int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
+    int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
+    bool abort_clean;         // the abort word has been zeroed since the workspace was bound
     char* ws;
     size_t ws_bound;
     bool have_forward;
@@ -164,6 +169,20 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     c->wDC = w;      w += up256(2 * B * H * 4);
     c->wLOGITS = w;  w += up256(M * (size_t)c->V * e);
     c->wROWLOSS = w; w += up256(M * 4);
+    // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
+    c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->abort_clean = false;
+    c->wUHT = w; c->wCNT = w;
+    if (c->st == DT_BF16 && rec_waves_for(c->H) > 0) {
+        const int NU = c->H / 32, tiles = (c->B + 31) / 32;
+        int nbg = 256 / (2 * NU);
+        if (nbg > tiles) nbg = tiles;
+        if (nbg < 1) nbg = 1;
+        c->rec_nbg = nbg;
+        c->rec_tiles = (tiles + nbg - 1) / nbg;
+        w += up256((size_t)c->L * 2 * 4 * H * H * 2);
+        c->wCNT = w;
+        w += up256(((size_t)2 * nbg * c->rec_tiles + 64) * 4);
+    }
     c->ws_bytes = w;
     c->ws = nullptr; c->ws_bound = 0; c->have_forward = false;
     c->prof = false; c->recs_used = 0;
@@ -208,6 +227,7 @@ int blstm_bind(blstm_ctx* c, void* workspace, size_t bytes) {
     c->ws = static_cast<char*>(workspace);
     c->ws_bound = bytes;
     c->have_forward = false;
+    c->abort_clean = false;
     return BLSTM_OK;
 }
 
@@ -236,6 +256,24 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
             d.C = AX; d.ldc = 8 * H; d.sC = 4 * H;
             d.bias = at(theta, ctx->off_b[0][l], e); d.sBias = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);
             RUN(PC_GEMM_INPUT, "input projection", launch_gemm(d, st));
+        }
+        if (ctx->rec_nbg > 0 && ctx->rec_path == 0) {   // all T frames of both directions in one launch
+            unsigned* cnt = reinterpret_cast<unsigned*>(ctx->ws + ctx->wCNT);
+            const int ncnt = 2 * ctx->rec_nbg * ctx->rec_tiles;
+            if (!ctx->abort_clean) {
+                RUN(PC_MISC, "abort word", launch_fill_u32(cnt + ncnt, 1, 0u, st));
+                ctx->abort_clean = true;
+            }
+            RUN(PC_MISC, "counters", launch_fill_u32(cnt, ncnt, 0u, st));
+            RecFwdArgs a{};
+            a.uh[0] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[0][l], e));
+            a.uh[1] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[1][l], e));
+            a.ax = AX; a.y = reinterpret_cast<unsigned short*>(Y); a.gates = reinterpret_cast<unsigned short*>(G); a.c = C;
+            a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
+            a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
+            bool launched = false;
+            RUN(PC_REC_FWD, "persistent recurrent forward", launch_rec_fwd(a, st, &launched));
+            if (launched) continue;
         }
         for (int n = 0; n < T; ++n) {
             const int t[2] = {n, T - 1 - n};
@@ -315,9 +353,9 @@ int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const
         d.M = V; d.N = Z; d.atrans = true; d.btrans = true;
         d.seg[0] = GemmSeg{U, z, V, Z, 0, 0, M};
         d.C = grad + ctx->off_ws; d.ldc = Z;
+        d.rowsum = grad + ctx->off_bs;                 // db_s = sum over frames of du
         RUN(PC_GEMM_SOFTMAX_BWD, "dW_s", launch_gemm(d, st));
     }
-    RUN(PC_COLSUM, "db_s", launch_colsum(U, V, M, V, grad + ctx->off_bs, nullptr, V, S, st));
     return BLSTM_OK;
 }
 
@@ -343,9 +381,9 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             d.M = P; d.N = 2 * H; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{dz, YL, P, 2 * H, 0, 0, M};
             d.C = grad + ctx->off_wp; d.ldc = 2 * H;
+            d.rowsum = grad + ctx->off_bp;             // db_p = sum over frames of dz
             RUN(PC_GEMM_WGRAD, "dW_p", launch_gemm(d, st));
         }
-        RUN(PC_COLSUM, "db_p", launch_colsum(dz, P, M, P, grad + ctx->off_bp, nullptr, P, S, st));
         {   // dy = dz W_p
             GemmDesc d = gemm_desc(S, S);
             d.M = M; d.N = 2 * H; d.btrans = true;
@@ -364,7 +402,26 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
         const char* Y = ctx->ws + ctx->wY[l];
         const char* G = ctx->ws + ctx->wG[l];
         const float* C = reinterpret_cast<const float*>(ctx->ws + ctx->wC[l]);
-        for (int n = T - 1; n >= 0; --n) {
+        bool rec_done = false;
+        if (ctx->rec_nbg > 0 && ctx->rec_path == 0) {
+            unsigned* cnt = reinterpret_cast<unsigned*>(ctx->ws + ctx->wCNT);
+            const int ncnt = 2 * ctx->rec_nbg * ctx->rec_tiles;
+            unsigned short* uht0 = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wUHT) + (size_t)l * 2 * 4 * H * H;
+            unsigned short* uht1 = uht0 + (size_t)4 * H * H;
+            RUN(PC_MISC, "U_h transpose", launch_transpose_uh(reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[0][l], e)),
+                                                              reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[1][l], e)),
+                                                              uht0, uht1, H, st));
+            RUN(PC_MISC, "counters", launch_fill_u32(cnt, ncnt, 0u, st));
+            RecBwdArgs a{};
+            a.uht[0] = uht0; a.uht[1] = uht1;
+            a.dy = reinterpret_cast<const unsigned short*>(dY);
+            a.gates = reinterpret_cast<const unsigned short*>(G); a.c = C;
+            a.da = reinterpret_cast<unsigned short*>(DA); a.dc = DC;
+            a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
+            a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
+            RUN(PC_REC_BWD, "persistent recurrent backward", launch_rec_bwd(a, st, &rec_done));
+        }
+        for (int n = T - 1; n >= 0 && !rec_done; --n) {
             const int t[2] = {n, T - 1 - n};
             const int tp[2] = {n - 1, T - n};
             CellBwdArgs a{};
@@ -395,6 +452,8 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             d.batch = 2; d.M = 4 * H; d.N = Din; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{DA, Xin, 8 * H, Din, 4 * H, 0, M};
             d.C = grad + ctx->off_wx[0][l]; d.ldc = Din; d.sC = (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]);
+            d.rowsum = grad + ctx->off_b[0][l];        // db = sum over frames of da
+            d.sRowsum = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);
             RUN(PC_GEMM_WGRAD, "dW_x", launch_gemm(d, st));
         }
         {   // dU_h = da^T h_prev: forward direction pairs da[t] with h[t-1], backward direction with h[t+1]
@@ -408,7 +467,6 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             d.C = grad + ctx->off_uh[0][l]; d.ldc = H; d.sC = (long long)(ctx->off_uh[1][l] - ctx->off_uh[0][l]);
             RUN(PC_GEMM_WGRAD, "dU_h", launch_gemm(d, st));
         }
-        RUN(PC_COLSUM, "db", launch_colsum(DA, 8 * H, M, 8 * H, grad + ctx->off_b[0][l], grad + ctx->off_b[1][l], 4 * H, S, st));
         if (l > 0) {   // dx = da_fwd W_x_fwd + da_bwd W_x_bwd, the gradient of the layer below's output
             GemmDesc d = gemm_desc(S, S);
             d.M = M; d.N = Din; d.btrans = true; d.nseg = 2;
@@ -471,6 +529,29 @@ int blstm_shadow_refresh(const float* theta, void* shadow, size_t n, void* strea
     if (!theta || !shadow) return fail(BLSTM_ERR_NULL, "blstm_shadow_refresh: null argument");
     if (!aligned16(theta) || !aligned16(shadow)) return fail(BLSTM_ERR_ALIGN, "blstm_shadow_refresh: pointers must be 16-byte aligned");
     return check_hip(launch_shadow(theta, static_cast<unsigned short*>(shadow), n, static_cast<hipStream_t>(stream)), "blstm_shadow_refresh");
+}
+
+int blstm_set_option(blstm_ctx* c, int option, int value) {
+    if (!c) return fail(BLSTM_ERR_NULL, "blstm_set_option: null argument");
+    if (option == BLSTM_OPT_RECURRENT_PATH && (value == 0 || value == 1)) { c->rec_path = value; return BLSTM_OK; }
+    return fail(BLSTM_ERR_DIM, "blstm_set_option: unknown option %d or value %d", option, value);
+}
+
+int blstm_device_status(blstm_ctx* c, void* stream) {
+    if (!c) return fail(BLSTM_ERR_NULL, "blstm_device_status: null argument");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return check_hip(e, "blstm_device_status");
+    if (!c->ws || c->rec_nbg == 0 || !c->abort_clean) return BLSTM_OK;
+    unsigned* word = reinterpret_cast<unsigned*>(c->ws + c->wCNT) + 2 * c->rec_nbg * c->rec_tiles;
+    unsigned v = 0;
+    e = hipMemcpy(&v, word, sizeof v, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return check_hip(e, "blstm_device_status");
+    if (v != 0) {
+        c->abort_clean = false;          // the next forward pass zeroes the word again
+        return fail(BLSTM_ERR_HIP, "a persistent recurrent kernel abandoned a wait: its workgroups were not co-resident");
+    }
+    return BLSTM_OK;
 }
 
 int blstm_profile_classes(void) { return PC_COUNT; }

@@ -38,8 +38,9 @@ struct Params {
     void* C; long long ldc;
     const void* bias;               // element type of the inputs
     const float* add; long long ldadd;
+    float* rowsum;                  // rowsum[m] = sum_k A(m,k) over segment 0, or null
     int M, N, ntm, ntn;
-    long long sA[2], sB[2], sC, sBias, sAdd;
+    long long sA[2], sB[2], sC, sBias, sAdd, sRowsum;
 };
 
 // ---- guarded element-wise fallbacks ------------------------------------------------
@@ -214,6 +215,17 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+    // Row sums of A ride along as one more product against a fragment of ones; only the
+    // workgroups of the first tile column, and in them the waves of the first half, do it.
+    const bool do_rs = P.rowsum != nullptr && tn == 0 && wn == 0;
+    f32x16_t rs[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) rs[i][e] = 0.0f;
+    const uint32_t one_w = sizeof(TI) == 2 ? 0x3F803F80u : 0x3F800000u;
+    const uint4 ones = make_uint4(one_w, one_w, one_w, one_w);
+
     int ntiles[2];
     ntiles[0] = (P.K[0] + BK - 1) / BK;
     ntiles[1] = P.nseg > 1 ? (P.K[1] + BK - 1) / BK : 0;
@@ -266,9 +278,24 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) mma<TI>(acc[i][j], af[i], bfr[j]);
+            if (do_rs && it < ntiles[0]) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) mma<TI>(rs[i], af[i], ones);
+            }
         }
         if (it + 1 < total) sstore(buf ^ 1);
         __syncthreads();
+    }
+
+    if (do_rs && (lane & 31) == 0) {
+        float* out = P.rowsum + z * P.sRowsum;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (row < P.M) out[row] = rs[i][e];
+            }
     }
 
     // Epilogue: accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32.
@@ -324,6 +351,7 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     P.C = d.C; P.ldc = d.ldc; P.sC = d.sC;
     P.bias = d.bias; P.sBias = d.sBias;
     P.add = d.add; P.ldadd = d.ldadd; P.sAdd = d.sAdd;
+    P.rowsum = d.rowsum; P.sRowsum = d.sRowsum;
     P.M = d.M; P.N = d.N;
     P.ntm = (d.M + BM - 1) / BM; P.ntn = (d.N + BN - 1) / BN;
     dim3 grid((unsigned)(P.ntm * P.ntn), 1, (unsigned)(d.batch > 0 ? d.batch : 1));

@@ -26,6 +26,8 @@ struct GemmDesc {
     long long sBias;
     const float* add;         // float [M][N] added to the product, or null
     long long ldadd, sAdd;
+    float* rowsum;            // rowsum[m] = sum_k A(m,k) of segment 0 (bias gradients), or null
+    long long sRowsum;
     int M, N, batch;
     bool atrans, btrans;
     DType in_type, out_type;  // in_type is the element type of A and B

@@ -35,16 +35,45 @@ struct CellBwdArgs {
 };
 hipError_t launch_cell_bwd(const CellBwdArgs& a, DType store, hipStream_t s);
 
+// ---- persistent recurrent kernels (bf16 storage, H a multiple of 128 up to 512) -------------------
+struct RecFwdArgs {
+    const unsigned short* uh[2];  // U_h per direction, [4H][H]
+    const float* ax;              // W_x x + b for every frame, [M][8H]
+    unsigned short* y;            // layer output h, [M][2H]
+    unsigned short* gates;        // gate activations, [M][8H]
+    float* c;                     // cell state, [M][2H]
+    unsigned* cnt;                // [2*nbg][tiles_per_group] counters, zero before the launch
+    unsigned* abort_word;         // raised when a wait ran out of time
+    unsigned long long limit_ticks;   // wait limit in ticks of the 100 MHz wall clock
+    int T, B, H, nbg, tiles_per_group;
+};
+struct RecBwdArgs {
+    const unsigned short* uht[2]; // U_h^T per direction, [H][4H]
+    const unsigned short* dy;     // dE/dh from above, [M][2H]
+    const unsigned short* gates;  // [M][8H]
+    const float* c;               // [M][2H]
+    unsigned short* da;           // dE/da, [M][8H]
+    float* dc;                    // carried dE/dc, [2][B][H]
+    unsigned* cnt;
+    unsigned* abort_word;
+    unsigned long long limit_ticks;
+    int T, B, H, nbg, tiles_per_group;
+};
+// Wavefronts per workgroup of the persistent kernels for this H, 0 if H is not supported.
+int rec_waves_for(int H);
+// *launched is false (and nothing was enqueued) when the grid cannot be co-resident on this device.
+hipError_t launch_rec_fwd(const RecFwdArgs& a, hipStream_t st, bool* launched);
+hipError_t launch_rec_bwd(const RecBwdArgs& a, hipStream_t st, bool* launched);
+hipError_t launch_transpose_uh(const unsigned short* src0, const unsigned short* src1, unsigned short* dst0,
+                               unsigned short* dst1, int H, hipStream_t st);
+hipError_t launch_fill_u32(unsigned* p, int n, unsigned v, hipStream_t st);
+
 // ---- softmax cross-entropy over rows of the logit matrix -----------------------------
 // u [M][V] (storage type) is overwritten by dE/du = s (p - onehot); row_loss[m] = -s log p[label].
 hipError_t launch_softmax_rows(void* u, long long ldu, const int32_t* labels, float* row_loss,
                                int M, int V, float s, DType store, hipStream_t st);
 // out[0] = sum_m v[m], one workgroup, fixed summation order.
 hipError_t launch_sum_to_scalar(const float* v, int M, float* out, hipStream_t st);
-
-// ---- column sums: out[n] = sum_m A[m][n]; columns >= split go to out_hi[n - split] -------------
-hipError_t launch_colsum(const void* A, long long lda, int M, int N, float* out_lo, float* out_hi, int split,
-                         DType store, hipStream_t st);
 
 // ---- weight update and replica averaging ---------------------------------------------
 hipError_t launch_sgd(float* theta, unsigned short* shadow, const float* grad, size_t n, float lr, float mu,

@@ -1,5 +1,4 @@
-// Row-wise softmax cross-entropy on a materialised logit matrix, fixed-order sums, and
-// column sums for the bias gradients.
+// Row-wise softmax cross-entropy on a materialised logit matrix, with fixed-order sums.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -48,24 +47,6 @@ __global__ __launch_bounds__(1024) void sum_to_scalar_kernel(const float* v, int
     if (threadIdx.x == 0) out[0] = acc;
 }
 
-// 64 columns x 4 row groups per workgroup; every column is summed in a fixed order.
-template <typename TS>
-__global__ __launch_bounds__(256) void colsum_kernel(const TS* A, long long lda, int M, int N,
-                                                     float* out_lo, float* out_hi, int split) {
-    __shared__ float sh[4][64];
-    const int cx = threadIdx.x & 63, rg = threadIdx.x >> 6;
-    const int n = blockIdx.x * 64 + cx;
-    float acc = 0.0f;
-    if (n < N)
-        for (int m = rg; m < M; m += 4) acc += ld_f(A + (long long)m * lda + n);
-    sh[rg][cx] = acc;
-    __syncthreads();
-    if (rg == 0 && n < N) {
-        float t = (sh[0][cx] + sh[1][cx]) + (sh[2][cx] + sh[3][cx]);
-        if (n < split) out_lo[n] = t; else out_hi[n - split] = t;
-    }
-}
-
 }  // namespace
 
 hipError_t launch_softmax_rows(void* u, long long ldu, const int32_t* labels, float* row_loss,
@@ -80,17 +61,6 @@ hipError_t launch_softmax_rows(void* u, long long ldu, const int32_t* labels, fl
 
 hipError_t launch_sum_to_scalar(const float* v, int M, float* out, hipStream_t st) {
     hipLaunchKernelGGL(sum_to_scalar_kernel, dim3(1), dim3(1024), 0, st, v, M, out);
-    return hipGetLastError();
-}
-
-hipError_t launch_colsum(const void* A, long long lda, int M, int N, float* out_lo, float* out_hi, int split,
-                         DType store, hipStream_t st) {
-    if (N <= 0) return hipSuccess;
-    dim3 grid((unsigned)((N + 63) / 64)), block(256);
-    if (store == DT_BF16)
-        hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, st, static_cast<const bf16_t*>(A), lda, M, N, out_lo, out_hi, split);
-    else
-        hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, st, static_cast<const float*>(A), lda, M, N, out_lo, out_hi, split);
     return hipGetLastError();
 }
 

@@ -16,13 +16,15 @@ from . import inputs
 class Learner:
     """Buffers of one learner: master weights, bf16 shadow, gradient, batch, workspace."""
 
-    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0):
+    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0, recurrent_path=0):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the HIP path has no CPU fallback")
         self.dims = dict(T=T, B=B, D=D, H=H, L=L, P=P, V=V)
         self.mode = mode
         self.device = torch.device(device)
         self.ctx = bl.blstm_create(T, B, D, H, L, P, V, mode, loss_scale)
+        if recurrent_path:
+            bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_RECURRENT_PATH, recurrent_path)
         self.n = bl.blstm_param_count(self.ctx)
         self.zdim = P if P > 0 else 2 * H
         self.act_dtype = torch.bfloat16 if mode == 1 else torch.float32
@@ -85,6 +87,10 @@ class Learner:
     def train_step(self, lr, stream=None):
         self.calgrad(stream)
         self.apply(lr, stream)
+
+    def check_status(self, stream=None):
+        """Synchronises and raises if a persistent kernel abandoned a wait."""
+        bl.blstm_device_status(self.ctx, stream)
 
     # ---- data out --------------------------------------------------------------------
     def loss_value(self) -> float:

@@ -42,17 +42,18 @@ def make_problem(dims, mode, seed, theta_scale=1.0):
     return dm, theta, x, labels
 
 
-def check_step(dims, mode, seed, lr=0.1, theta_scale=1.0, tol=None, check_update=True):
+def check_step(dims, mode, seed, lr=0.1, theta_scale=1.0, tol=None, check_update=True, recurrent_path=0):
     """One full training step on the GPU against the oracle; returns the worst relative error."""
     from paper_1904_04956_amd.harness import Learner
     tol = TOL[mode] if tol is None else tol
     dm, theta, x, labels = make_problem(dims, mode, seed, theta_scale)
     say(f"case dims={dims} mode={mode} seed={seed}")
-    lrn = Learner(mode=mode, **dims)
+    lrn = Learner(mode=mode, recurrent_path=recurrent_path, **dims)
     try:
         lrn.set_theta(theta)
         lrn.set_batch(x, labels)
         lrn.calgrad()
+        lrn.check_status()
         z_gpu = lrn.z_numpy()
         loss_gpu = lrn.loss_value()
         g_gpu = lrn.grad_numpy()
@@ -133,6 +134,37 @@ def test_loss_scale_argument_fp32():
 ])
 def test_shapes_bf16(dims):
     check_step(dims, 1, seed=78, theta_scale=2.0)
+
+
+@pytest.mark.parametrize("dims", [
+    dict(T=4, B=300, D=64, H=512, L=1, P=64, V=200),        # ten batch tiles over eight groups: two tiles per workgroup, some empty
+    dict(T=6, B=45, D=32, H=256, L=2, P=0, V=120),          # two wavefronts per workgroup, ragged batch tile
+    dict(T=2, B=64, D=16, H=128, L=1, P=16, V=40),          # one wavefront per workgroup
+])
+def test_persistent_recurrent_kernels_bf16(dims):
+    check_step(dims, 1, seed=79, theta_scale=2.0)
+
+
+def test_persistent_and_stepwise_paths_agree():
+    from paper_1904_04956_amd.harness import Learner
+    dims = dict(T=7, B=70, D=48, H=256, L=2, P=32, V=150)
+    dm, theta, x, labels = make_problem(dims, 1, 80, 2.0)
+    res = []
+    for path in (0, 1):
+        lrn = Learner(mode=1, recurrent_path=path, **dims)
+        lrn.set_theta(theta); lrn.set_batch(x, labels); lrn.calgrad(); lrn.check_status()
+        res.append((lrn.loss_value(), lrn.grad_numpy().copy(), lrn.z_numpy().copy()))
+        lrn.close()
+    # same arithmetic up to the order of the float sums inside a dot product
+    assert abs(res[0][0] - res[1][0]) <= 2e-3 * abs(res[1][0])
+    assert rel_err(res[0][2], res[1][2]) <= 2e-2
+    assert rel_err(res[0][1], res[1][1]) <= 2e-2
+
+
+def test_paper_shaped_workload_bf16_stepwise_path():
+    w = inputs.WORKLOADS["paper4x512"]
+    d = w.dims(); d["B"] = 64
+    check_step(d, 1, w.seed, lr=w.lr, recurrent_path=1)
 
 
 def test_paper_shaped_workload_bf16_full_size():
