@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel-class event pass")
+    ap.add_argument("--rec-sync", type=int, default=-1, help="exchange protocol of the persistent kernels (library default if < 0)")
+    ap.add_argument("--rec-path", type=int, default=0, help="1 = one launch per frame")
     ap.add_argument("--mix-replicas", type=int, default=16, help="replicas of the separate adpsgd_mix measurement")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -81,7 +83,9 @@ def main():
     T, B = d["T"], d["B"]
     bf = w.mode == 1
 
-    lrn = Learner(mode=w.mode, **d)
+    lrn = Learner(mode=w.mode, recurrent_path=args.rec_path, **d)
+    if args.rec_sync >= 0:
+        bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_RECURRENT_SYNC, args.rec_sync)
     theta = inputs.make_theta(lrn.n, w.seed, bf16=bf)
     x, labels = inputs.make_batch(T, B, d["D"], d["V"], w.seed, bf16=bf)
     lrn.set_theta(theta)
@@ -107,6 +111,7 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = 1e3 * dt / args.steps
     frames_per_s = T * B * args.steps / dt
+    lrn.check_status()
     loss = lrn.loss_value()
     fpf = flop_per_frame(d["D"], d["H"], d["L"], d["P"], d["V"])
     peak = PEAK_BF16_MFMA if bf else PEAK_FP32_MFMA

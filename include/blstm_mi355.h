@@ -114,6 +114,12 @@ int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
    persistent kernel where the shape allows it (mode 1, H a multiple of 128 up to 512, grid
    co-resident on the device), 1 forces one launch per frame everywhere. */
 #define BLSTM_OPT_RECURRENT_PATH 1
+/* BLSTM_OPT_RECURRENT_SYNC (default 1): how the workgroups of a persistent kernel exchange h / dE/da
+   between frames.  0: plain accesses ordered by agent-scope release/acquire fences around a counter.
+   1: the exchanged tensor is pre-filled with a bf16 NaN pattern no result can take; elements are
+   stored write-through and loaded cache-bypassing at agent scope, and a consumer proceeds once
+   none of the elements it needs still holds the pattern (each element is its own ready flag). */
+#define BLSTM_OPT_RECURRENT_SYNC 2
 int blstm_set_option(blstm_ctx* ctx, int option, int value);
 
 /* The only call that synchronises: waits for `stream`, then reports whether a persistent kernel

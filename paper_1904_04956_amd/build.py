@@ -30,9 +30,31 @@ def hipcc() -> str:
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     cmd = [hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    if src == "recurrent.hip":
+        cmd.append("-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
+    lines = [l for l in r.stderr.splitlines() if noise not in l]
+    if src == "recurrent.hip":
+        # a persistent kernel whose registers spill to scratch memory is rejected: keep them resident
+        name = ""
+        for l in lines:
+            if "Function Name:" in l:
+                name = l.split("Function Name:")[1].split()[0]
+            if "ScratchSize [bytes/lane]:" in l and "rec_" in name:
+                if int(l.split("ScratchSize [bytes/lane]:")[1].split()[0]) != 0:
+                    raise RuntimeError(f"persistent kernel {name} spills to scratch memory")
+        keep, skip = [], 0
+        for l in lines:                      # drop the remarks and the source excerpts printed under them
+            if "remark:" in l:
+                skip = 2
+                continue
+            if skip and (l.lstrip().startswith("|") or l.lstrip()[:1].isdigit() or "^" in l):
+                skip -= 1
+                continue
+            keep.append(l)
+        lines = keep
+    err = "\n".join(lines)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():

@@ -61,6 +61,7 @@ struct blstm_ctx {
     size_t wAX, wPRE, wDA, wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, ws_bytes;
     int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
+    int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
     char* ws;
     size_t ws_bound;
@@ -170,7 +171,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     c->wLOGITS = w;  w += up256(M * (size_t)c->V * e);
     c->wROWLOSS = w; w += up256(M * 4);
     // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
-    c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->abort_clean = false;
+    c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false;
     c->wUHT = w; c->wCNT = w;
     if (c->st == DT_BF16 && rec_waves_for(c->H) > 0) {
         const int NU = c->H / 32, tiles = (c->B + 31) / 32;
@@ -271,8 +272,9 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
             a.ax = AX; a.y = reinterpret_cast<unsigned short*>(Y); a.gates = reinterpret_cast<unsigned short*>(G); a.c = C;
             a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
+            if (ctx->rec_sync == 1) RUN(PC_MISC, "sentinel fill of h", launch_fill_bytes16(Y, (size_t)M * 2 * H * e, 0xFFFFFFFFu, st));
             bool launched = false;
-            RUN(PC_REC_FWD, "persistent recurrent forward", launch_rec_fwd(a, st, &launched));
+            RUN(PC_REC_FWD, "persistent recurrent forward", launch_rec_fwd(a, ctx->rec_sync == 1, st, &launched));
             if (launched) continue;
         }
         for (int n = 0; n < T; ++n) {
@@ -419,7 +421,8 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             a.da = reinterpret_cast<unsigned short*>(DA); a.dc = DC;
             a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
-            RUN(PC_REC_BWD, "persistent recurrent backward", launch_rec_bwd(a, st, &rec_done));
+            if (ctx->rec_sync == 1) RUN(PC_MISC, "sentinel fill of da", launch_fill_bytes16(DA, (size_t)M * 8 * H * e, 0xFFFFFFFFu, st));
+            RUN(PC_REC_BWD, "persistent recurrent backward", launch_rec_bwd(a, ctx->rec_sync == 1, st, &rec_done));
         }
         for (int n = T - 1; n >= 0 && !rec_done; --n) {
             const int t[2] = {n, T - 1 - n};
@@ -534,6 +537,7 @@ int blstm_shadow_refresh(const float* theta, void* shadow, size_t n, void* strea
 int blstm_set_option(blstm_ctx* c, int option, int value) {
     if (!c) return fail(BLSTM_ERR_NULL, "blstm_set_option: null argument");
     if (option == BLSTM_OPT_RECURRENT_PATH && (value == 0 || value == 1)) { c->rec_path = value; return BLSTM_OK; }
+    if (option == BLSTM_OPT_RECURRENT_SYNC && (value == 0 || value == 1)) { c->rec_sync = value; return BLSTM_OK; }
     return fail(BLSTM_ERR_DIM, "blstm_set_option: unknown option %d or value %d", option, value);
 }
 

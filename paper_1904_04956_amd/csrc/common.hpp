@@ -33,6 +33,11 @@ __device__ __forceinline__ void st_f(bf16_t* p, float v) { *p = f2bf(v); }
 __device__ __forceinline__ float sigmoidf_(float a) { return 1.0f / (1.0f + expf(-a)); }
 __device__ __forceinline__ float tanhf_(float a) { return tanhf(a); }
 
+// Hardware exp2/rcp forms for the bf16 path: absolute error of a few 1e-7, far below the
+// 2^-9 relative step of the bf16 values they feed; both saturate cleanly for large |a|.
+__device__ __forceinline__ float fast_sigmoid(float a) { return __frcp_rn(1.0f + __expf(-a)); }
+__device__ __forceinline__ float fast_tanh(float a) { return 1.0f - 2.0f * __frcp_rn(__expf(2.0f * a) + 1.0f); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -39,7 +39,7 @@ hipError_t launch_cell_bwd(const CellBwdArgs& a, DType store, hipStream_t s);
 struct RecFwdArgs {
     const unsigned short* uh[2];  // U_h per direction, [4H][H]
     const float* ax;              // W_x x + b for every frame, [M][8H]
-    unsigned short* y;            // layer output h, [M][2H]
+    unsigned short* y;            // layer output h, [M][2H]; pre-filled with 0xFFFF in sentinel mode
     unsigned short* gates;        // gate activations, [M][8H]
     float* c;                     // cell state, [M][2H]
     unsigned* cnt;                // [2*nbg][tiles_per_group] counters, zero before the launch
@@ -52,7 +52,7 @@ struct RecBwdArgs {
     const unsigned short* dy;     // dE/dh from above, [M][2H]
     const unsigned short* gates;  // [M][8H]
     const float* c;               // [M][2H]
-    unsigned short* da;           // dE/da, [M][8H]
+    unsigned short* da;           // dE/da, [M][8H]; pre-filled with 0xFFFF in sentinel mode
     float* dc;                    // carried dE/dc, [2][B][H]
     unsigned* cnt;
     unsigned* abort_word;
@@ -62,11 +62,13 @@ struct RecBwdArgs {
 // Wavefronts per workgroup of the persistent kernels for this H, 0 if H is not supported.
 int rec_waves_for(int H);
 // *launched is false (and nothing was enqueued) when the grid cannot be co-resident on this device.
-hipError_t launch_rec_fwd(const RecFwdArgs& a, hipStream_t st, bool* launched);
-hipError_t launch_rec_bwd(const RecBwdArgs& a, hipStream_t st, bool* launched);
+hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bool* launched);
+hipError_t launch_rec_bwd(const RecBwdArgs& a, bool sentinel, hipStream_t st, bool* launched);
 hipError_t launch_transpose_uh(const unsigned short* src0, const unsigned short* src1, unsigned short* dst0,
                                unsigned short* dst1, int H, hipStream_t st);
 hipError_t launch_fill_u32(unsigned* p, int n, unsigned v, hipStream_t st);
+// Fills bytes/16 16-byte words with the 32-bit pattern v.
+hipError_t launch_fill_bytes16(void* p, size_t bytes, unsigned v, hipStream_t st);
 
 // ---- softmax cross-entropy over rows of the logit matrix -----------------------------
 // u [M][V] (storage type) is overwritten by dE/du = s (p - onehot); row_loss[m] = -s log p[label].

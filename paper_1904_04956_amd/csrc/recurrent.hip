@@ -7,10 +7,19 @@
 // frame's gate gradients (backward) by its slice, reduces the NW partial accumulators through
 // LDS, applies the cell arithmetic with all four gates of a unit in one lane, and writes its
 // 32 columns.  The NU = H/32 workgroups that share a batch tile exchange these columns through
-// global memory; a per-(group, tile) counter, incremented with release semantics at agent
-// scope after a workgroup's stores and polled with acquire semantics before the next frame's
-// loads, orders the exchange.  Every wait is bounded by a wall-clock limit: on expiry the
-// workgroup raises a global abort word that all other waits observe, so every wave exits.
+// global memory, in one of two ways:
+//
+//   SENTINEL  The exchanged tensor (h, or dE/da) is filled with the bf16 bit pattern 0xFFFF (a
+//             NaN no finite value converts to) before the launch.  Producers store write-through
+//             at agent scope, consumers load cache-bypassing at agent scope and take a chunk only
+//             when none of its elements is the sentinel.  Each element is written once and is
+//             its own ready flag: no counters, no fences, no barriers beyond the LDS reduction.
+//   FENCED    Plain stores and loads ordered by a per-(group, tile) counter that is incremented
+//             with agent-scope release semantics and polled with acquire semantics.
+//
+// Every wait is bounded by a wall-clock limit.  On expiry the wave raises a global abort word;
+// every later wait returns at once when it sees the word, so all waves run to the end of the
+// kernel (with invalid results, which blstm_device_status reports).
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -18,49 +27,117 @@ namespace blstm {
 namespace {
 
 constexpr int KW = 128;                                  // contraction elements per wavefront (forward)
+constexpr unsigned SENT16 = 0xFFFFu;
 
 __device__ __forceinline__ f32x16_t mfma_bf16(const uint4& a, const uint4& b, f32x16_t c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
-// Waits until *cnt >= target.  Thread 0 polls; returns true for the whole workgroup if the wait
-// was abandoned (time limit or another workgroup's abort).  Contains two barriers.
-__device__ __forceinline__ bool wait_counter(unsigned* cnt, unsigned target, unsigned* abort_word,
-                                             unsigned long long limit_ticks, int* s_flag) {
+__device__ __forceinline__ unsigned ld_coh_u32(const unsigned* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// ---- FENCED protocol ----------------------------------------------------------------------------
+// Waits until *cnt >= target; thread 0 polls.  One barrier inside.
+__device__ __forceinline__ void wait_counter(unsigned* cnt, unsigned target, unsigned* abort_word, unsigned long long limit_ticks) {
     if (threadIdx.x == 0) {
-        int bad = 0;
         const unsigned long long t0 = wall_clock64();
         unsigned it = 0;
-        while (__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        while (ld_coh_u32(cnt) < target) {
             __builtin_amdgcn_s_sleep(1);
             if ((++it & 63u) == 0) {
-                if (__hip_atomic_load(abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { bad = 1; break; }
+                if (ld_coh_u32(abort_word) != 0) break;
                 if (wall_clock64() - t0 > limit_ticks) {
                     __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    bad = 1;
                     break;
                 }
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        *s_flag = bad;
     }
     __syncthreads();
-    const bool bad = *s_flag != 0;
-    __syncthreads();
-    return bad;
 }
-
-// After the workgroup's stores: make them visible at agent scope, then count this workgroup in.
+// After the workgroup's stores: the barrier orders them before thread 0's agent-scope release.
 __device__ __forceinline__ void signal_counter(unsigned* cnt) {
     __syncthreads();
     if (threadIdx.x == 0) __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// ---- SENTINEL protocol --------------------------------------------------------------------------
+__device__ __forceinline__ void st_coh_bf16(bf16_t* p, float v) {
+    bf16_t b = f2bf(v);
+    if (b == SENT16) b = 0x7FC0;                         // a NaN result must not look like "not written yet"
+    __hip_atomic_store(p, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint4 ld_coh_16B(const bf16_t* p) {
+    const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+    const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
+}
+__device__ __forceinline__ bool has_sentinel(unsigned w) { return (w & 0xFFFFu) == SENT16 || (w >> 16) == SENT16; }
+__device__ __forceinline__ bool has_sentinel(const uint4& v) {
+    return has_sentinel(v.x) || has_sentinel(v.y) || has_sentinel(v.z) || has_sentinel(v.w);
+}
+
+// Bounded wait of one wave.  `probe` points, for the lanes with probing set, at one element of each
+// producer's block: a cheap first look before the full loads.  Returns true if the wait was
+// abandoned (time limit, or the abort word raised by anyone).  Wave-uniform control flow.
+__device__ __forceinline__ bool wait_probe(const bf16_t* probe, bool probing, unsigned* abort_word,
+                                           unsigned long long limit_ticks) {
+    const unsigned long long t0 = wall_clock64();
+    unsigned it = 0;
+    for (;;) {
+        bool ready = true;
+        if (probing) ready = __hip_atomic_load(probe, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != SENT16;
+        if (__all(ready)) return false;
+        __builtin_amdgcn_s_sleep(1);
+        if ((++it & 31u) == 0) {
+            if (ld_coh_u32(abort_word) != 0) return true;
+            if (wall_clock64() - t0 > limit_ticks) {
+                __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return true;
+            }
+        }
+    }
+}
+
+template <int NQ>
+__device__ __forceinline__ void load_chunks(uint4 (&frag)[NQ], const bf16_t* p, bool valid) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) frag[q] = valid ? ld_coh_16B(p + q * 16) : make_uint4(0, 0, 0, 0);
+}
+template <int NQ>
+__device__ __forceinline__ bool all_written(const uint4 (&frag)[NQ]) {
+    bool ok = true;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) ok = ok && !has_sentinel(frag[q]);
+    return __all(ok);
+}
+// The chunks in frag were loaded once; reloads them until no element of any lane is the sentinel
+// (or the wait is abandoned).  Normally the first check passes.
+template <int NQ>
+__device__ __forceinline__ bool ensure_written(uint4 (&frag)[NQ], const bf16_t* p, bool valid, bool give_up,
+                                               unsigned* abort_word, unsigned long long limit_ticks) {
+    if (give_up || all_written<NQ>(frag)) return give_up;
+    const unsigned long long t0 = wall_clock64();
+    unsigned it = 0;
+    for (;;) {
+        __builtin_amdgcn_s_sleep(1);
+        load_chunks<NQ>(frag, p, valid);
+        if (all_written<NQ>(frag)) return false;
+        if ((++it & 31u) == 0) {
+            if (ld_coh_u32(abort_word) != 0) return true;
+            if (wall_clock64() - t0 > limit_ticks) {
+                __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return true;
+            }
+        }
+    }
+}
+
 struct GroupMap { int d, u, bg, group; };
 
 // Workgroups that exchange data sit on one XCD when ids are dealt round-robin over eight XCDs
-// (a performance assumption only; correctness rests on the agent-scope ordering above).
+// (a performance assumption only; correctness rests on the protocols above).
 __device__ __forceinline__ GroupMap map_block(int NU, int nbg) {
     const int ngroups = 2 * nbg;
     const int x = blockIdx.x;
@@ -78,19 +155,38 @@ __device__ __forceinline__ GroupMap map_block(int NU, int nbg) {
     return m;
 }
 
+// First attempt at the exchanged chunks: ordinary cached loads.  Every element is either the
+// sentinel or its final value (it is written once, after the pre-fill), so whatever cache level
+// answers, a chunk without sentinels is correct; anything else is re-read cache-bypassing by
+// ensure_written.
+template <int NQ>
+__device__ __forceinline__ void load_chunks_cached(uint4 (&frag)[NQ], const bf16_t* p, bool valid) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) frag[q] = valid ? *reinterpret_cast<const uint4*>(p + q * 16) : make_uint4(0, 0, 0, 0);
+}
+
+// Number of 32-row batch tiles of this workgroup's group that lie inside the batch.
+__device__ __forceinline__ int tiles_in_batch(int bg, int tiles_per_group, int B) {
+    const int first = bg * tiles_per_group * 32;
+    if (first >= B) return 0;
+    const int n = (B - first + 31) / 32;
+    return n < tiles_per_group ? n : tiles_per_group;
+}
+
 // ------------------------------------------------------------------------------ forward
-template <int NW>
+template <int NW, bool SENTINEL>
 __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     constexpr int EPT = 16 / NW;                         // accumulator registers (batch rows) per thread
     constexpr int KSTEPS = KW / 16;                      // MFMA steps per gate per wavefront
     extern __shared__ float lds[];                       // [NW][4][4][64][4] partial accumulators
-    __shared__ int s_flag;
     const int H = a.H, B = a.B, T = a.T;
     const int NU = H / 32;
     const GroupMap gm = map_block(NU, a.nbg);
     const int d = gm.d, u = gm.u;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
+    const int ntl = tiles_in_batch(gm.bg, a.tiles_per_group, B);
+    if (ntl == 0) return;
 
     // this wavefront's slice of U_h as B-fragments: unit row l32 of each gate, 8 consecutive k per lane
     uint4 bfrag[4][KSTEPS];
@@ -104,98 +200,150 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     }
     unsigned* cnt = a.cnt + (size_t)gm.group * a.tiles_per_group;
     const int j = u * 32 + l32;                          // this thread's hidden unit
-    bool dead = false;
+    float4* l4 = reinterpret_cast<float4*>(lds);
 
-    for (int n = 0; n < T && !dead; ++n) {
+    // Per-item inputs that do not depend on the exchange (a_x of the frame, previous cell state) are
+    // loaded one item ahead, so that their HBM latency never sits on the frame-to-frame path.
+    // Item = (visited frame n, batch tile i); this thread's EPT batch rows are accumulator
+    // registers r = EPT*wave + e.
+    auto issue_inputs = [&](int item, float (&ax)[EPT][4], float (&cp)[EPT]) {
+        const int n = item / ntl, i = item - n * ntl;
         const int t = d ? T - 1 - n : n;
         const int tp = d ? T - n : n - 1;
-        for (int i = 0; i < a.tiles_per_group; ++i) {
-            const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
-            if (b0 >= B) break;
-            // this thread's EPT batch rows: accumulator register r = EPT*wave + e
-            float ax[EPT][4], cp[EPT];
+        const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) {
-                const int r = EPT * wave + e;
-                const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                const bool ok = b < B;
-                const float* p = a.ax + ((size_t)t * B + (ok ? b : 0)) * 8 * H + (size_t)d * 4 * H + j;
+        for (int e = 0; e < EPT; ++e) {
+            const int r = EPT * wave + e;
+            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            const bool ok = b < B;
+            const float* p = a.ax + ((size_t)t * B + (ok ? b : 0)) * 8 * H + (size_t)d * 4 * H + j;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) ax[e][g] = ok ? p[(size_t)g * H] : 0.0f;
-                cp[e] = (ok && n > 0) ? a.c[((size_t)tp * B + b) * 2 * H + (size_t)d * H + j] : 0.0f;
+            for (int g = 0; g < 4; ++g) ax[e][g] = ok ? p[(size_t)g * H] : 0.0f;
+            cp[e] = (ok && n > 0) ? a.c[((size_t)tp * B + b) * 2 * H + (size_t)d * H + j] : 0.0f;
+        }
+    };
+
+    const int nitems = T * ntl;
+    float ax[EPT][4], cp[EPT];
+    issue_inputs(0, ax, cp);
+    for (int item = 0; item < nitems; ++item) {
+        const int n = item / ntl, i = item - n * ntl;
+        const int t = d ? T - 1 - n : n;
+        const int tp = d ? T - n : n - 1;
+        const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
+        float axn[EPT][4], cpn[EPT];
+        float sum[EPT][4];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) sum[e][g] = 0.0f;
+        if (n > 0) {
+            // previous h of this batch tile: row l32, 8 consecutive k per lane
+            const int row = b0 + l32;
+            const bool valid = row < B;
+            const bf16_t* hp = a.y + ((size_t)tp * B + (valid ? row : 0)) * 2 * H + (size_t)d * H + wave * KW + 8 * lh;
+            uint4 afrag[KSTEPS];
+            if (SENTINEL) {
+                // one probe per producing workgroup of this wavefront's k-range: its last unit, last valid row
+                const int prow = min(b0 + 31, B - 1);
+                const bf16_t* probe = a.y + ((size_t)tp * B + prow) * 2 * H + (size_t)d * H + wave * KW + (lane & 3) * 32 + 31;
+                const bool gu = wait_probe(probe, lane < KW / 32, a.abort_word, a.limit_ticks);
+                asm volatile("" ::: "memory");
+                load_chunks_cached<KSTEPS>(afrag, hp, valid);
+                if (item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
+                ensure_written<KSTEPS>(afrag, hp, valid, gu, a.abort_word, a.limit_ticks);
+            } else {
+                wait_counter(cnt + i, (unsigned)(NU * n), a.abort_word, a.limit_ticks);
+#pragma unroll
+                for (int q = 0; q < KSTEPS; ++q)
+                    afrag[q] = valid ? *reinterpret_cast<const uint4*>(hp + q * 16) : make_uint4(0, 0, 0, 0);
+                if (item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
             }
-            float sum[EPT][4];
+            f32x16_t acc[4];
 #pragma unroll
-            for (int e = 0; e < EPT; ++e)
+            for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) sum[e][g] = 0.0f;
-            if (n > 0) {
-                if (wait_counter(cnt + i, (unsigned)(NU * n), a.abort_word, a.limit_ticks, &s_flag)) { dead = true; break; }
-                // previous h of this batch tile: row l32, 8 consecutive k per lane
-                const int row = b0 + l32;
-                const bf16_t* hp = a.y + ((size_t)tp * B + (row < B ? row : 0)) * 2 * H + (size_t)d * H + wave * KW + 8 * lh;
-                uint4 afrag[KSTEPS];
+                for (int e = 0; e < 16; ++e) acc[g][e] = 0.0f;
 #pragma unroll
-                for (int q = 0; q < KSTEPS; ++q)
-                    afrag[q] = row < B ? *reinterpret_cast<const uint4*>(hp + q * 16) : make_uint4(0, 0, 0, 0);
-                f32x16_t acc[4];
+            for (int q = 0; q < KSTEPS; ++q)
 #pragma unroll
-                for (int g = 0; g < 4; ++g)
+                for (int g = 0; g < 4; ++g) acc[g] = mfma_bf16(afrag[q], bfrag[g][q], acc[g]);
+            // partial accumulators -> LDS as [wave][gate][reg/4][lane][reg%4]
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[g][e] = 0.0f;
+            for (int g = 0; g < 4; ++g)
 #pragma unroll
-                for (int q = 0; q < KSTEPS; ++q)
+                for (int rq = 0; rq < 4; ++rq)
+                    l4[((wave * 4 + g) * 4 + rq) * 64 + lane] =
+                        make_float4(acc[g][4 * rq], acc[g][4 * rq + 1], acc[g][4 * rq + 2], acc[g][4 * rq + 3]);
+            __syncthreads();
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) acc[g] = mfma_bf16(afrag[q], bfrag[g][q], acc[g]);
-                // partial accumulators -> LDS as [wave][gate][reg/4][lane][reg%4]
-                float4* l4 = reinterpret_cast<float4*>(lds);
+            for (int w2 = 0; w2 < NW; ++w2)
 #pragma unroll
-                for (int g = 0; g < 4; ++g)
+                for (int g = 0; g < 4; ++g) {
+                    if (EPT >= 4) {
 #pragma unroll
-                    for (int rq = 0; rq < 4; ++rq)
-                        l4[((wave * 4 + g) * 4 + rq) * 64 + lane] =
-                            make_float4(acc[g][4 * rq], acc[g][4 * rq + 1], acc[g][4 * rq + 2], acc[g][4 * rq + 3]);
-                __syncthreads();
-#pragma unroll
-                for (int w2 = 0; w2 < NW; ++w2)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g)
+                        for (int e4 = 0; e4 < EPT / 4; ++e4) {
+                            const float4 v = l4[((w2 * 4 + g) * 4 + (EPT / 4) * wave + e4) * 64 + lane];
+                            sum[4 * e4][g] += v.x; sum[4 * e4 + 1][g] += v.y; sum[4 * e4 + 2][g] += v.z; sum[4 * e4 + 3][g] += v.w;
+                        }
+                    } else {
 #pragma unroll
                         for (int e = 0; e < EPT; ++e) {
                             const int r = EPT * wave + e;
                             sum[e][g] += lds[((((w2 * 4 + g) * 4 + (r >> 2)) * 64 + lane) << 2) + (r & 3)];
                         }
-            }
-#pragma unroll
-            for (int e = 0; e < EPT; ++e) {
-                const int r = EPT * wave + e;
-                const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (b < B) {
-                    const float gi = sigmoidf_(ax[e][0] + sum[e][0]);
-                    const float gf = sigmoidf_(ax[e][1] + sum[e][1]);
-                    const float gg = tanhf_(ax[e][2] + sum[e][2]);
-                    const float go = sigmoidf_(ax[e][3] + sum[e][3]);
-                    const float c = gf * cp[e] + gi * gg;
-                    const float h = go * tanhf_(c);
-                    const size_t m = (size_t)t * B + b;
-                    a.c[m * 2 * H + (size_t)d * H + j] = c;
-                    bf16_t* gp = a.gates + m * 8 * H + (size_t)d * 4 * H + j;
-                    gp[0] = f2bf(gi); gp[(size_t)H] = f2bf(gf); gp[(size_t)2 * H] = f2bf(gg); gp[(size_t)3 * H] = f2bf(go);
-                    a.y[m * 2 * H + (size_t)d * H + j] = f2bf(h);
+                    }
                 }
+        } else if (item + 1 < nitems) {
+            issue_inputs(item + 1, axn, cpn);
+        }
+        // cell arithmetic; h goes out first because it is all the other workgroups wait for
+        float gi[EPT], gf[EPT], gg[EPT], go[EPT], cn[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int r = EPT * wave + e;
+            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            gi[e] = fast_sigmoid(ax[e][0] + sum[e][0]);
+            gf[e] = fast_sigmoid(ax[e][1] + sum[e][1]);
+            gg[e] = fast_tanh(ax[e][2] + sum[e][2]);
+            go[e] = fast_sigmoid(ax[e][3] + sum[e][3]);
+            cn[e] = gf[e] * cp[e] + gi[e] * gg[e];
+            const float h = go[e] * fast_tanh(cn[e]);
+            if (b < B) {
+                bf16_t* yp = a.y + ((size_t)t * B + b) * 2 * H + (size_t)d * H + j;
+                if (SENTINEL) st_coh_bf16(yp, h); else *yp = f2bf(h);
             }
-            signal_counter(cnt + i);                     // also the barrier that frees the LDS buffer
+        }
+        if (SENTINEL) __syncthreads();                   // frees the LDS buffer for the next item
+        else signal_counter(cnt + i);                    // barrier inside: same role
+        // saved for the backward pass only: off the critical path of the exchange
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int r = EPT * wave + e;
+            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (b < B) {
+                const size_t m = (size_t)t * B + b;
+                a.c[m * 2 * H + (size_t)d * H + j] = cn[e];
+                bf16_t* gp = a.gates + m * 8 * H + (size_t)d * 4 * H + j;
+                gp[0] = f2bf(gi[e]); gp[(size_t)H] = f2bf(gf[e]); gp[(size_t)2 * H] = f2bf(gg[e]); gp[(size_t)3 * H] = f2bf(go[e]);
+            }
+        }
+        // next item's inputs; with one tile per workgroup its previous cell state is the one just computed
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) ax[e][g] = axn[e][g];
+            cp[e] = (ntl == 1) ? cn[e] : cpn[e];
         }
     }
 }
 
 // ------------------------------------------------------------------------------ backward
-template <int NW>
+template <int NW, bool SENTINEL>
 __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     constexpr int EPT = 16 / NW;
     constexpr int KSTEPS = 4 * KW / 16;                  // the contraction runs over the 4H gate rows
     extern __shared__ float lds[];                       // [NW][4][64][4]
-    __shared__ int s_flag;
     const int H = a.H, B = a.B, T = a.T;
     const int NU = H / 32;
     const GroupMap gm = map_block(NU, a.nbg);
@@ -203,6 +351,8 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
     const int KWB = 4 * H / NW;                          // gate rows per wavefront (= 4 * KW)
+    const int ntl = tiles_in_batch(gm.bg, a.tiles_per_group, B);
+    if (ntl == 0) return;
 
     // U_h^T slice: output unit l32, 8 consecutive gate rows per lane
     uint4 bfrag[KSTEPS];
@@ -214,76 +364,139 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     }
     unsigned* cnt = a.cnt + (size_t)gm.group * a.tiles_per_group;
     const int j = u * 32 + l32;
-    bool dead = false;
+    float4* l4 = reinterpret_cast<float4*>(lds);
 
-    for (int n = T - 1; n >= 0 && !dead; --n) {
+    // Saved activations of an item, loaded one item ahead (raw bf16 for the gates and dy).
+    struct Inputs { bf16_t g[EPT][4]; bf16_t dy[EPT]; float c[EPT], cp[EPT], dcr[EPT]; };
+    auto issue_inputs = [&](int item, Inputs& in) {
+        const int ni = item / ntl, i = item - ni * ntl;
+        const int n = T - 1 - ni;
         const int t = d ? T - 1 - n : n;
-        const int tp = d ? T - n : n - 1;                // frame visited before t (its c is c_prev)
+        const int tp = d ? T - n : n - 1;
+        const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int r = EPT * wave + e;
+            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            const bool ok = b < B;
+            const size_t m = (size_t)t * B + (ok ? b : 0);
+            const bf16_t* gp = a.gates + m * 8 * H + (size_t)d * 4 * H + j;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) in.g[e][g] = ok ? gp[(size_t)g * H] : (bf16_t)0;
+            in.c[e] = ok ? a.c[m * 2 * H + (size_t)d * H + j] : 0.0f;
+            in.cp[e] = (ok && n > 0) ? a.c[((size_t)tp * B + b) * 2 * H + (size_t)d * H + j] : 0.0f;
+            in.dy[e] = ok ? a.dy[m * 2 * H + (size_t)d * H + j] : (bf16_t)0;
+            in.dcr[e] = (ok && n < T - 1) ? a.dc[((size_t)d * B + b) * H + j] : 0.0f;
+        }
+    };
+
+    // With 16 rows per thread (one wavefront per workgroup) two sets of inputs do not fit in
+    // registers: that variant loads each item's inputs at the item's start instead.
+    constexpr bool AHEAD = EPT <= 8;
+    const int nitems = T * ntl;
+    Inputs cur;
+    if (AHEAD) issue_inputs(0, cur);
+    for (int item = 0; item < nitems; ++item) {
+        if (!AHEAD) issue_inputs(item, cur);
+        const int ni = item / ntl, i = item - ni * ntl;
+        const int n = T - 1 - ni;
+        const int t = d ? T - 1 - n : n;
         const int tn = d ? T - 2 - n : n + 1;            // frame visited after t (its da feeds dh)
-        for (int i = 0; i < a.tiles_per_group; ++i) {
-            const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
-            if (b0 >= B) break;
-            float dh[EPT], gi[EPT], gf[EPT], gg[EPT], go[EPT], cc[EPT], cp[EPT], dcr[EPT];
+        const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
+        Inputs nxt;
+        float dh[EPT];
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) {
-                const int r = EPT * wave + e;
-                const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                const bool ok = b < B;
-                const size_t m = (size_t)t * B + (ok ? b : 0);
-                const bf16_t* gp = a.gates + m * 8 * H + (size_t)d * 4 * H + j;
-                gi[e] = ok ? bf2f(gp[0]) : 0.0f; gf[e] = ok ? bf2f(gp[(size_t)H]) : 0.0f;
-                gg[e] = ok ? bf2f(gp[(size_t)2 * H]) : 0.0f; go[e] = ok ? bf2f(gp[(size_t)3 * H]) : 0.0f;
-                cc[e] = ok ? a.c[m * 2 * H + (size_t)d * H + j] : 0.0f;
-                cp[e] = (ok && n > 0) ? a.c[((size_t)tp * B + b) * 2 * H + (size_t)d * H + j] : 0.0f;
-                dh[e] = ok ? bf2f(a.dy[m * 2 * H + (size_t)d * H + j]) : 0.0f;
-                dcr[e] = (ok && n < T - 1) ? a.dc[((size_t)d * B + b) * H + j] : 0.0f;
-            }
-            if (n < T - 1) {
-                if (wait_counter(cnt + i, (unsigned)(NU * (T - 1 - n)), a.abort_word, a.limit_ticks, &s_flag)) { dead = true; break; }
-                const int row = b0 + l32;
-                const bf16_t* ap = a.da + ((size_t)tn * B + (row < B ? row : 0)) * 8 * H + (size_t)d * 4 * H + wave * KWB + 8 * lh;
-                f32x16_t acc;
+        for (int e = 0; e < EPT; ++e) dh[e] = 0.0f;
+        if (n < T - 1) {
+            const int row = b0 + l32;
+            const bool valid = row < B;
+            const bf16_t* ap = a.da + ((size_t)tn * B + (valid ? row : 0)) * 8 * H + (size_t)d * 4 * H + wave * KWB + 8 * lh;
+            f32x16_t acc;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+            for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+            if (SENTINEL) {
+                // the gate rows of this wavefront come from KWB/32 producers: probe each one's last unit,
+                // then stream the slabs of 128 gate rows with the next slab's loads in flight
+                const int prow = min(b0 + 31, B - 1);
+                const bf16_t* probe = a.da + ((size_t)tn * B + prow) * 8 * H + (size_t)d * 4 * H + wave * KWB + (lane & 15) * 32 + 31;
+                bool gu = wait_probe(probe, lane < 16, a.abort_word, a.limit_ticks);
+                asm volatile("" ::: "memory");
+                uint4 afrag[2][8];
+                load_chunks_cached<8>(afrag[0], ap, valid);
+#pragma unroll
+                for (int sl = 0; sl < KSTEPS / 8; ++sl) {
+                    if (sl + 1 < KSTEPS / 8) load_chunks_cached<8>(afrag[(sl + 1) & 1], ap + (sl + 1) * 128, valid);
+                    else if (AHEAD && item + 1 < nitems) issue_inputs(item + 1, nxt);
+                    gu = ensure_written<8>(afrag[sl & 1], ap + sl * 128, valid, gu, a.abort_word, a.limit_ticks);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) acc = mfma_bf16(afrag[sl & 1][q], bfrag[sl * 8 + q], acc);
+                }
+            } else {
+                wait_counter(cnt + i, (unsigned)(NU * (T - 1 - n)), a.abort_word, a.limit_ticks);
 #pragma unroll
                 for (int q0 = 0; q0 < KSTEPS; q0 += 8) {
                     uint4 afrag[8];
 #pragma unroll
                     for (int q = 0; q < 8; ++q)
-                        afrag[q] = row < B ? *reinterpret_cast<const uint4*>(ap + (q0 + q) * 16) : make_uint4(0, 0, 0, 0);
+                        afrag[q] = valid ? *reinterpret_cast<const uint4*>(ap + (q0 + q) * 16) : make_uint4(0, 0, 0, 0);
+                    if (AHEAD && q0 + 8 >= KSTEPS && item + 1 < nitems) issue_inputs(item + 1, nxt);
 #pragma unroll
                     for (int q = 0; q < 8; ++q) acc = mfma_bf16(afrag[q], bfrag[q0 + q], acc);
                 }
-                float4* l4 = reinterpret_cast<float4*>(lds);
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq)
-                    l4[(wave * 4 + rq) * 64 + lane] = make_float4(acc[4 * rq], acc[4 * rq + 1], acc[4 * rq + 2], acc[4 * rq + 3]);
-                __syncthreads();
-#pragma unroll
-                for (int w2 = 0; w2 < NW; ++w2)
-#pragma unroll
-                    for (int e = 0; e < EPT; ++e) {
-                        const int r = EPT * wave + e;
-                        dh[e] += lds[(((w2 * 4 + (r >> 2)) * 64 + lane) << 2) + (r & 3)];
-                    }
             }
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) {
-                const int r = EPT * wave + e;
-                const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (b < B) {
-                    const float tc = tanhf_(cc[e]);
-                    const float dc = dh[e] * go[e] * (1.0f - tc * tc) + dcr[e];
-                    const float da_o = dh[e] * tc * go[e] * (1.0f - go[e]);
-                    const float da_i = dc * gg[e] * gi[e] * (1.0f - gi[e]);
-                    const float da_f = dc * cp[e] * gf[e] * (1.0f - gf[e]);
-                    const float da_g = dc * gi[e] * (1.0f - gg[e] * gg[e]);
-                    a.dc[((size_t)d * B + b) * H + j] = dc * gf[e];
-                    bf16_t* dp = a.da + ((size_t)t * B + b) * 8 * H + (size_t)d * 4 * H + j;
+            for (int rq = 0; rq < 4; ++rq)
+                l4[(wave * 4 + rq) * 64 + lane] = make_float4(acc[4 * rq], acc[4 * rq + 1], acc[4 * rq + 2], acc[4 * rq + 3]);
+            __syncthreads();
+#pragma unroll
+            for (int w2 = 0; w2 < NW; ++w2)
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) {
+                    const int r = EPT * wave + e;
+                    dh[e] += lds[(((w2 * 4 + (r >> 2)) * 64 + lane) << 2) + (r & 3)];
+                }
+        } else if (AHEAD && item + 1 < nitems) {
+            issue_inputs(item + 1, nxt);
+        }
+        float dcf[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int r = EPT * wave + e;
+            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            const float gi = bf2f(cur.g[e][0]), gf = bf2f(cur.g[e][1]), gg = bf2f(cur.g[e][2]), go = bf2f(cur.g[e][3]);
+            const float dht = dh[e] + bf2f(cur.dy[e]);
+            const float tc = fast_tanh(cur.c[e]);
+            const float dc = dht * go * (1.0f - tc * tc) + cur.dcr[e];
+            const float da_o = dht * tc * go * (1.0f - go);
+            const float da_i = dc * gg * gi * (1.0f - gi);
+            const float da_f = dc * cur.cp[e] * gf * (1.0f - gf);
+            const float da_g = dc * gi * (1.0f - gg * gg);
+            dcf[e] = dc * gf;
+            if (b < B) {
+                bf16_t* dp = a.da + ((size_t)t * B + b) * 8 * H + (size_t)d * 4 * H + j;
+                if (SENTINEL) {
+                    st_coh_bf16(dp, da_i); st_coh_bf16(dp + (size_t)H, da_f);
+                    st_coh_bf16(dp + (size_t)2 * H, da_g); st_coh_bf16(dp + (size_t)3 * H, da_o);
+                } else {
                     dp[0] = f2bf(da_i); dp[(size_t)H] = f2bf(da_f); dp[(size_t)2 * H] = f2bf(da_g); dp[(size_t)3 * H] = f2bf(da_o);
                 }
             }
-            signal_counter(cnt + i);
+        }
+        if (SENTINEL) __syncthreads();
+        else signal_counter(cnt + i);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int r = EPT * wave + e;
+            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (b < B) a.dc[((size_t)d * B + b) * H + j] = dcf[e];
+        }
+        // next item's inputs; with one tile per workgroup its carried dE/dc is the one just computed
+        if (AHEAD) {
+            cur = nxt;
+            if (ntl == 1) {
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) cur.dcr[e] = dcf[e];
+            }
         }
     }
 }
@@ -300,6 +513,12 @@ __global__ __launch_bounds__(256) void transpose_uh_kernel(const bf16_t* src0, c
     for (int rr = ty; rr < 32; rr += 8) dst[(size_t)(c0 + rr) * 4 * H + r0 + tx] = tile[tx][rr];
 }
 
+// p[0..n) = v for 16-byte words, grid-stride.
+__global__ __launch_bounds__(256) void fill_u128_kernel(uint4* p, size_t n, unsigned v) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const uint4 w = make_uint4(v, v, v, v);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = w;
+}
 __global__ void fill_u32_kernel(unsigned* p, int n, unsigned v) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -324,6 +543,27 @@ hipError_t prepare(K kernel, int threads, size_t dyn_lds, int grid, bool* fits) 
     return hipSuccess;
 }
 
+template <int NW, bool S>
+hipError_t run_fwd(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
+    const size_t lds = (size_t)NW * 4 * 4 * 64 * 16;
+    bool fits = false;
+    hipError_t e = prepare(rec_fwd_kernel<NW, S>, 64 * NW, lds, grid, &fits);
+    if (e != hipSuccess || !fits) return e;
+    hipLaunchKernelGGL((rec_fwd_kernel<NW, S>), dim3(grid), dim3(64 * NW), lds, st, a);
+    *launched = true;
+    return hipGetLastError();
+}
+template <int NW, bool S>
+hipError_t run_bwd(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
+    const size_t lds = (size_t)NW * 4 * 64 * 16;
+    bool fits = false;
+    hipError_t e = prepare(rec_bwd_kernel<NW, S>, 64 * NW, lds, grid, &fits);
+    if (e != hipSuccess || !fits) return e;
+    hipLaunchKernelGGL((rec_bwd_kernel<NW, S>), dim3(grid), dim3(64 * NW), lds, st, a);
+    *launched = true;
+    return hipGetLastError();
+}
+
 }  // namespace
 
 int rec_waves_for(int H) {
@@ -338,56 +578,41 @@ hipError_t launch_fill_u32(unsigned* p, int n, unsigned v, hipStream_t st) {
     return hipGetLastError();
 }
 
+hipError_t launch_fill_bytes16(void* p, size_t bytes, unsigned v, hipStream_t st) {
+    const size_t n = bytes / 16;
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_u128_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<uint4*>(p), n, v);
+    return hipGetLastError();
+}
+
 hipError_t launch_transpose_uh(const unsigned short* src0, const unsigned short* src1, unsigned short* dst0,
                                unsigned short* dst1, int H, hipStream_t st) {
     hipLaunchKernelGGL(transpose_uh_kernel, dim3(H / 32, 4 * H / 32, 2), dim3(256), 0, st, src0, src1, dst0, dst1, H);
     return hipGetLastError();
 }
 
-hipError_t launch_rec_fwd(const RecFwdArgs& a, hipStream_t st, bool* launched) {
+hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bool* launched) {
     *launched = false;
-    const int nw = rec_waves_for(a.H);
-    if (nw == 0) return hipSuccess;
     const int grid = 2 * a.nbg * (a.H / 32);
-    const size_t lds = (size_t)nw * 4 * 4 * 64 * 16;
-    bool fits = false;
-    hipError_t e;
-#define BLSTM_REC_CASE(NWV)                                                                         \
-    case NWV:                                                                                       \
-        e = prepare(rec_fwd_kernel<NWV>, 64 * NWV, lds, grid, &fits);                               \
-        if (e != hipSuccess || !fits) return e;                                                     \
-        hipLaunchKernelGGL(rec_fwd_kernel<NWV>, dim3(grid), dim3(64 * NWV), lds, st, a);            \
-        break;
-    switch (nw) {
-        BLSTM_REC_CASE(1) BLSTM_REC_CASE(2) BLSTM_REC_CASE(4)
+    switch (rec_waves_for(a.H)) {
+        case 1: return sentinel ? run_fwd<1, true>(a, grid, st, launched) : run_fwd<1, false>(a, grid, st, launched);
+        case 2: return sentinel ? run_fwd<2, true>(a, grid, st, launched) : run_fwd<2, false>(a, grid, st, launched);
+        case 4: return sentinel ? run_fwd<4, true>(a, grid, st, launched) : run_fwd<4, false>(a, grid, st, launched);
         default: return hipSuccess;
     }
-#undef BLSTM_REC_CASE
-    *launched = true;
-    return hipGetLastError();
 }
 
-hipError_t launch_rec_bwd(const RecBwdArgs& a, hipStream_t st, bool* launched) {
+hipError_t launch_rec_bwd(const RecBwdArgs& a, bool sentinel, hipStream_t st, bool* launched) {
     *launched = false;
-    const int nw = rec_waves_for(a.H);
-    if (nw == 0) return hipSuccess;
     const int grid = 2 * a.nbg * (a.H / 32);
-    const size_t lds = (size_t)nw * 4 * 64 * 16;
-    bool fits = false;
-    hipError_t e;
-#define BLSTM_REC_CASE(NWV)                                                                         \
-    case NWV:                                                                                       \
-        e = prepare(rec_bwd_kernel<NWV>, 64 * NWV, lds, grid, &fits);                               \
-        if (e != hipSuccess || !fits) return e;                                                     \
-        hipLaunchKernelGGL(rec_bwd_kernel<NWV>, dim3(grid), dim3(64 * NWV), lds, st, a);            \
-        break;
-    switch (nw) {
-        BLSTM_REC_CASE(1) BLSTM_REC_CASE(2) BLSTM_REC_CASE(4)
+    switch (rec_waves_for(a.H)) {
+        case 1: return sentinel ? run_bwd<1, true>(a, grid, st, launched) : run_bwd<1, false>(a, grid, st, launched);
+        case 2: return sentinel ? run_bwd<2, true>(a, grid, st, launched) : run_bwd<2, false>(a, grid, st, launched);
+        case 4: return sentinel ? run_bwd<4, true>(a, grid, st, launched) : run_bwd<4, false>(a, grid, st, launched);
         default: return hipSuccess;
     }
-#undef BLSTM_REC_CASE
-    *launched = true;
-    return hipGetLastError();
 }
 
 }  // namespace blstm

@@ -42,13 +42,14 @@ def make_problem(dims, mode, seed, theta_scale=1.0):
     return dm, theta, x, labels
 
 
-def check_step(dims, mode, seed, lr=0.1, theta_scale=1.0, tol=None, check_update=True, recurrent_path=0):
+def check_step(dims, mode, seed, lr=0.1, theta_scale=1.0, tol=None, check_update=True, recurrent_path=0,
+               recurrent_sync=None):
     """One full training step on the GPU against the oracle; returns the worst relative error."""
     from paper_1904_04956_amd.harness import Learner
     tol = TOL[mode] if tol is None else tol
     dm, theta, x, labels = make_problem(dims, mode, seed, theta_scale)
     say(f"case dims={dims} mode={mode} seed={seed}")
-    lrn = Learner(mode=mode, recurrent_path=recurrent_path, **dims)
+    lrn = Learner(mode=mode, recurrent_path=recurrent_path, recurrent_sync=recurrent_sync, **dims)
     try:
         lrn.set_theta(theta)
         lrn.set_batch(x, labels)
@@ -141,8 +142,27 @@ def test_shapes_bf16(dims):
     dict(T=6, B=45, D=32, H=256, L=2, P=0, V=120),          # two wavefronts per workgroup, ragged batch tile
     dict(T=2, B=64, D=16, H=128, L=1, P=16, V=40),          # one wavefront per workgroup
 ])
-def test_persistent_recurrent_kernels_bf16(dims):
-    check_step(dims, 1, seed=79, theta_scale=2.0)
+@pytest.mark.parametrize("sync", [0, 1])
+def test_persistent_recurrent_kernels_bf16(dims, sync):
+    check_step(dims, 1, seed=79, theta_scale=2.0, recurrent_sync=sync)
+
+
+def test_exchange_protocols_agree_bit_for_bit():
+    # both protocols order the same arithmetic: any stale or torn read would show as a difference
+    from paper_1904_04956_amd.harness import Learner
+    dims = dict(T=21, B=96, D=64, H=512, L=2, P=64, V=300)
+    dm, theta, x, labels = make_problem(dims, 1, 81, 2.0)
+    ref = None
+    for sync in (0, 1, 1, 1):
+        lrn = Learner(mode=1, recurrent_sync=sync, **dims)
+        lrn.set_theta(theta); lrn.set_batch(x, labels)
+        for _ in range(5):
+            lrn.calgrad(); lrn.check_status()
+            out = (lrn.loss_value(), lrn.grad_numpy().copy())
+            if ref is None:
+                ref = out
+            assert out[0] == ref[0] and np.array_equal(out[1], ref[1])
+        lrn.close()
 
 
 def test_persistent_and_stepwise_paths_agree():
