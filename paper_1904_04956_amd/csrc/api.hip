@@ -58,7 +58,7 @@ struct blstm_ctx {
     size_t off_wp, off_bp, off_ws, off_bs;
     // workspace (byte offsets)
     std::vector<size_t> wY, wG, wC;
-    size_t wAX, wPRE, wDA, wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, ws_bytes;
+    size_t wAX, wPRE, wDA, wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, part_bytes, ws_bytes;
     int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
@@ -106,9 +106,11 @@ int check_hip(hipError_t e, const char* what) {
         if (e_ != hipSuccess) return check_hip(e_, what);            \
     } while (0)
 
-GemmDesc gemm_desc(DType in, DType out) {
+GemmDesc gemm_desc(const blstm_ctx* c, DType in, DType out) {
     GemmDesc d{};
     d.nseg = 1; d.batch = 1; d.in_type = in; d.out_type = out;
+    d.partial = reinterpret_cast<float*>(c->ws + c->wPART);
+    d.partial_bytes = c->part_bytes;
     return d;
 }
 
@@ -184,6 +186,18 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
         c->wCNT = w;
         w += up256(((size_t)2 * nbg * c->rec_tiles + 64) * 4);
     }
+    {   // split-K scratch: the largest need among the products with a small output
+        const DType S = c->st;
+        size_t need = 0;
+        auto upd = [&](int m, int n, int k, int batch) { size_t b = gemm_partial_bytes(m, n, k, batch, S); if (b > need) need = b; };
+        upd(c->M, c->zdim, c->V, 1);                              // dz
+        upd(c->V, c->zdim, c->M, 1);                              // dW_s
+        if (c->P > 0) { upd(c->P, 2 * c->H, c->M, 1); upd(c->M, 2 * c->H, c->P, 1); }
+        for (int l = 0; l < c->L; ++l) { upd(4 * c->H, c->din(l), c->M, 2); upd(4 * c->H, c->H, (c->T - 1) * c->B, 2); }
+        upd(c->B, c->H, 4 * c->H, 2);                             // recurrent gradient of the step-by-step path
+        c->wPART = w; c->part_bytes = up256(need);
+        w += c->part_bytes;
+    }
     c->ws_bytes = w;
     c->ws = nullptr; c->ws_bound = 0; c->have_forward = false;
     c->prof = false; c->recs_used = 0;
@@ -250,7 +264,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
         char* G = ctx->ws + ctx->wG[l];
         float* C = reinterpret_cast<float*>(ctx->ws + ctx->wC[l]);
         {   // a_x = W_x x + b for every frame, both directions
-            GemmDesc d = gemm_desc(S, DT_F32);
+            GemmDesc d = gemm_desc(ctx, S, DT_F32);
             d.batch = 2; d.M = M; d.N = 4 * H;
             d.seg[0] = GemmSeg{Xin, at(theta, ctx->off_wx[0][l], e), Din, Din, 0,
                                (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]), Din};
@@ -281,7 +295,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
             const int t[2] = {n, T - 1 - n};
             const int tp[2] = {n - 1, T - n};
             if (n > 0) {   // a = a_x + U_h h_prev
-                GemmDesc d = gemm_desc(S, DT_F32);
+                GemmDesc d = gemm_desc(ctx, S, DT_F32);
                 d.batch = 2; d.M = B; d.N = 4 * H;
                 const char* A0 = Y + ((size_t)tp[0] * B * 2 * H) * e;
                 const char* A1 = Y + ((size_t)tp[1] * B * 2 * H + H) * e;
@@ -308,7 +322,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
     }
     const char* YL = ctx->ws + ctx->wY[ctx->L - 1];
     if (ctx->P > 0) {
-        GemmDesc d = gemm_desc(S, S);
+        GemmDesc d = gemm_desc(ctx, S, S);
         d.M = M; d.N = ctx->P;
         d.seg[0] = GemmSeg{YL, at(theta, ctx->off_wp, e), 2 * H, 2 * H, 0, 0, 2 * H};
         d.C = z_out; d.ldc = ctx->P;
@@ -334,7 +348,7 @@ int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const
     char* U = ctx->ws + ctx->wLOGITS;
     float* row_loss = reinterpret_cast<float*>(ctx->ws + ctx->wROWLOSS);
     {   // u = W_s z + b_s
-        GemmDesc d = gemm_desc(S, S);
+        GemmDesc d = gemm_desc(ctx, S, S);
         d.M = M; d.N = V;
         d.seg[0] = GemmSeg{z, at(theta, ctx->off_ws, e), Z, Z, 0, 0, Z};
         d.C = U; d.ldc = V;
@@ -344,14 +358,14 @@ int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const
     RUN(PC_SOFTMAX_ROWS, "softmax rows", launch_softmax_rows(U, V, labels, row_loss, M, V, ctx->s, S, st));
     RUN(PC_MISC, "loss sum", launch_sum_to_scalar(row_loss, M, loss_dev, st));
     {   // dz = du W_s
-        GemmDesc d = gemm_desc(S, S);
+        GemmDesc d = gemm_desc(ctx, S, S);
         d.M = M; d.N = Z; d.btrans = true;
         d.seg[0] = GemmSeg{U, at(theta, ctx->off_ws, e), V, Z, 0, 0, V};
         d.C = dz; d.ldc = Z;
         RUN(PC_GEMM_SOFTMAX_BWD, "dz", launch_gemm(d, st));
     }
     {   // dW_s = du^T z
-        GemmDesc d = gemm_desc(S, DT_F32);
+        GemmDesc d = gemm_desc(ctx, S, DT_F32);
         d.M = V; d.N = Z; d.atrans = true; d.btrans = true;
         d.seg[0] = GemmSeg{U, z, V, Z, 0, 0, M};
         d.C = grad + ctx->off_ws; d.ldc = Z;
@@ -379,7 +393,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
     if (P > 0) {
         const char* YL = ctx->ws + ctx->wY[ctx->L - 1];
         {   // dW_p = dz^T y
-            GemmDesc d = gemm_desc(S, DT_F32);
+            GemmDesc d = gemm_desc(ctx, S, DT_F32);
             d.M = P; d.N = 2 * H; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{dz, YL, P, 2 * H, 0, 0, M};
             d.C = grad + ctx->off_wp; d.ldc = 2 * H;
@@ -387,7 +401,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             RUN(PC_GEMM_WGRAD, "dW_p", launch_gemm(d, st));
         }
         {   // dy = dz W_p
-            GemmDesc d = gemm_desc(S, S);
+            GemmDesc d = gemm_desc(ctx, S, S);
             d.M = M; d.N = 2 * H; d.btrans = true;
             d.seg[0] = GemmSeg{dz, at(theta, ctx->off_wp, e), P, 2 * H, 0, 0, P};
             d.C = ctx->ws + ctx->wDY[0]; d.ldc = 2 * H;
@@ -440,7 +454,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             }
             RUN(PC_CELL_BWD, "cell backward", launch_cell_bwd(a, S, st));
             if (n > 0) {   // dh_rec = da U_h
-                GemmDesc d = gemm_desc(S, DT_F32);
+                GemmDesc d = gemm_desc(ctx, S, DT_F32);
                 d.batch = 2; d.M = B; d.N = H; d.btrans = true;
                 const char* A0 = DA + ((size_t)t[0] * B * 8 * H) * e;
                 const char* A1 = DA + ((size_t)t[1] * B * 8 * H + 4 * H) * e;
@@ -451,7 +465,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             }
         }
         {   // dW_x = da^T x, both directions
-            GemmDesc d = gemm_desc(S, DT_F32);
+            GemmDesc d = gemm_desc(ctx, S, DT_F32);
             d.batch = 2; d.M = 4 * H; d.N = Din; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{DA, Xin, 8 * H, Din, 4 * H, 0, M};
             d.C = grad + ctx->off_wx[0][l]; d.ldc = Din; d.sC = (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]);
@@ -460,7 +474,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             RUN(PC_GEMM_WGRAD, "dW_x", launch_gemm(d, st));
         }
         {   // dU_h = da^T h_prev: forward direction pairs da[t] with h[t-1], backward direction with h[t+1]
-            GemmDesc d = gemm_desc(S, DT_F32);
+            GemmDesc d = gemm_desc(ctx, S, DT_F32);
             d.batch = 2; d.M = 4 * H; d.N = H; d.atrans = true; d.btrans = true;
             const char* A0 = DA + ((size_t)B * 8 * H) * e;
             const char* A1 = DA + ((size_t)4 * H) * e;
@@ -471,7 +485,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             RUN(PC_GEMM_WGRAD, "dU_h", launch_gemm(d, st));
         }
         if (l > 0) {   // dx = da_fwd W_x_fwd + da_bwd W_x_bwd, the gradient of the layer below's output
-            GemmDesc d = gemm_desc(S, S);
+            GemmDesc d = gemm_desc(ctx, S, S);
             d.M = M; d.N = Din; d.btrans = true; d.nseg = 2;
             d.seg[0] = GemmSeg{DA, at(theta, ctx->off_wx[0][l], e), 8 * H, Din, 0, 0, 4 * H};
             d.seg[1] = GemmSeg{DA + (size_t)4 * H * e, at(theta, ctx->off_wx[1][l], e), 8 * H, Din, 0, 0, 4 * H};

@@ -1,21 +1,29 @@
 // C(m,n) = sum_k A(m,k) B(n,k) (+ bias[n]) (+ add[m][n]) on the matrix cores of gfx950.
 //
-// One workgroup of four wavefronts owns a 128x128 tile of C; each wavefront owns a
-// 64x64 quarter as 2x2 MFMA 32x32 accumulators.  A K-slab of eight 16-byte chunks per
-// row (64 bf16 or 32 float) is staged through LDS, double buffered, with the next
-// slab's global loads in flight while the current one is multiplied.  Operands whose
-// contraction index is the slow one in memory ("transposed") are loaded along their
-// fast index and transposed in registers on the way to LDS, so all three forms of a
-// training step's products (X W^T, dA W, dA^T X) run through the same inner loop.
-// LDS rows are XOR-swizzled at chunk granularity so that both the row-wise stores and
-// the MFMA fragment reads spread over the banks.
+// One workgroup of four wavefronts (2 x 2) owns a (64 TM) x (64 TN) tile of C; each wavefront
+// owns a (32 TM) x (32 TN) part as TM x TN MFMA 32x32 accumulators.  Two tile shapes are built:
+// 256x256 (TM = TN = 4: each LDS fragment feeds four products, which keeps LDS traffic at half
+// of its bandwidth when the matrix cores are busy) for the large products, and 128x128 for
+// products whose output has too few large tiles to fill 256 compute units.  A K-slab of eight
+// 16-byte chunks per row (64 bf16 or 32 float) is staged through LDS, double buffered, with the
+// next slab's global loads in flight while the current one is multiplied, and the fragments of
+// the next sub-step read from LDS while the current products issue.  Operands whose contraction
+// index is the slow one in memory ("transposed") are loaded along their fast index and
+// transposed in registers on the way to LDS, so all three forms of a training step's products
+// (X W^T, dA W, dA^T X) run through the same inner loop.  LDS rows are XOR-swizzled at chunk
+// granularity so that both the row-wise stores and the MFMA fragment reads spread over the
+// banks.  Products with a small output and a long contraction are split along K over
+// blockIdx.y into float partial tiles that a second kernel sums in a fixed order.
 #include "common.hpp"
 #include "gemm.hpp"
 
 namespace blstm {
 namespace {
 
-constexpr int BM = 128, BN = 128, NTHREADS = 256;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int NTHREADS = 256;
 constexpr int CHUNKS = 8;                       // 16-byte chunks per LDS row and K-slab
 
 template <typename T> struct Vec { };
@@ -39,7 +47,9 @@ struct Params {
     const void* bias;               // element type of the inputs
     const float* add; long long ldadd;
     float* rowsum;                  // rowsum[m] = sum_k A(m,k) over segment 0, or null
-    int M, N, ntm, ntn;
+    float* partial;                 // split-K: float [batch][splits][M][N], or null
+    float* rs_partial;              // split-K: float [batch][splits][M] row sums
+    int M, N, ntm, ntn, splits;
     long long sA[2], sB[2], sC, sBias, sAdd, sRowsum;
 };
 
@@ -64,12 +74,12 @@ __device__ __forceinline__ void load_elems<float, 4>(uint32_t* out, const float*
 
 // ---- global -> registers ---------------------------------------------------------
 // K is the fast index in memory: thread owns chunks c = tid + 256 i, row = c / 8, chunk = c % 8.
-template <typename T>
-__device__ __forceinline__ void gload_kfast(uint4 (&r)[4], const Operand& op, int row0, int K, int k0, int tid) {
+template <typename T, int NCH>
+__device__ __forceinline__ void gload_kfast(uint4 (&r)[NCH], const Operand& op, int row0, int K, int k0, int tid) {
     constexpr int VEC = Vec<T>::N;
     const T* base = static_cast<const T*>(op.p);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NCH; ++i) {
         int c = tid + NTHREADS * i;
         int row = row0 + (c >> 3);
         int k = k0 + (c & 7) * VEC;
@@ -92,74 +102,101 @@ __device__ __forceinline__ void gload_kfast(uint4 (&r)[4], const Operand& op, in
     }
 }
 
-// The non-contracted index is the fast one in memory.  Thread owns rows rq*4..rq*4+3
-// (rq = tid % 32) and the K-chunk tid / 32: VEC loads of four consecutive rows each.
-template <typename T>
-__device__ __forceinline__ void gload_rowfast(uint4 (&r)[4], const Operand& op, int row0, int K, int k0, int tid) {
+// The non-contracted index is the fast one in memory.  Per pass of 128 rows a thread owns rows
+// rq*4..rq*4+3 (rq = tid % 32) and the K-chunk tid / 32: VEC loads of four consecutive rows each.
+template <typename T, int NCH>
+__device__ __forceinline__ void gload_rowfast(uint4 (&r)[NCH], const Operand& op, int row0, int K, int k0, int tid) {
     constexpr int VEC = Vec<T>::N;
     const T* base = static_cast<const T*>(op.p);
-    const int row = row0 + (tid & 31) * 4;
     const int kb = k0 + (tid >> 5) * VEC;
-    uint32_t w[16];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) {
-        constexpr int WPL = 16 / VEC;                    // 32-bit words per load: 4 (float) or 2 (bf16)
-        uint32_t* o = &w[i * WPL];
+    for (int pass = 0; pass < NCH / 4; ++pass) {
+        const int row = row0 + pass * 128 + (tid & 31) * 4;
+        uint32_t w[16];
 #pragma unroll
-        for (int q = 0; q < WPL; ++q) o[q] = 0u;
-        int k = kb + i;
-        if (k < K && row < op.rows) {
-            const T* p = base + (long long)k * op.ld + row;
-            if ((op.fast & 1) && row + 4 <= op.rows) {
-                if (sizeof(T) == 4) { uint4 v = *reinterpret_cast<const uint4*>(p); o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
-                else { uint2 v = *reinterpret_cast<const uint2*>(p); o[0] = v.x; o[1] = v.y; }
-            } else {
-                load_elems<T, 4>(o, p, op.rows - row);
+        for (int i = 0; i < VEC; ++i) {
+            constexpr int WPL = 16 / VEC;                // 32-bit words per load: 4 (float) or 2 (bf16)
+            uint32_t* o = &w[i * WPL];
+#pragma unroll
+            for (int q = 0; q < WPL; ++q) o[q] = 0u;
+            int k = kb + i;
+            if (k < K && row < op.rows) {
+                const T* p = base + (long long)k * op.ld + row;
+                if ((op.fast & 1) && row + 4 <= op.rows) {
+                    if (sizeof(T) == 4) { uint4 v = *reinterpret_cast<const uint4*>(p); o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
+                    else { uint2 v = *reinterpret_cast<const uint2*>(p); o[0] = v.x; o[1] = v.y; }
+                } else {
+                    load_elems<T, 4>(o, p, op.rows - row);
+                }
             }
         }
-    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
-}
-
-// ---- registers -> LDS -------------------------------------------------------------
-__device__ __forceinline__ void sstore_kfast(uint4* s, const uint4 (&r)[4], int tid) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int c = tid + NTHREADS * i;
-        int row = c >> 3;
-        s[row * CHUNKS + ((c & 7) ^ swz(row))] = r[i];
+        for (int i = 0; i < 4; ++i) r[pass * 4 + i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
     }
 }
 
-template <typename T>
-__device__ __forceinline__ void sstore_rowfast(uint4* s, const uint4 (&r)[4], int tid) {
-    const int rq = tid & 31, kc = tid >> 5;
-    if (sizeof(T) == 4) {
-        // r[i] = rows 0..3 at k = i  ->  chunk of row j = (r[0][j], r[1][j], r[2][j], r[3][j])
-        const uint32_t a[4][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
-                                  {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w}};
+// ---- unguarded forms: tile fully inside the matrices, K a multiple of the slab, aligned -------
+// `base` is uniform (tile origin and slab applied, in bytes); `voff` is this thread's byte offset.
+template <typename T, int NCH>
+__device__ __forceinline__ void gload_kfast_fast(uint4 (&r)[NCH], const char* base, long long rowstep, uint32_t voff) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int row = rq * 4 + j;
-            s[row * CHUNKS + (kc ^ swz(row))] = make_uint4(a[0][j], a[1][j], a[2][j], a[3][j]);
-        }
-    } else {
-        // load i (k = i) holds rows 0..3 as two words: L[i][0] = rows 0,1 ; L[i][1] = rows 2,3
-        const uint32_t L[8][2] = {{r[0].x, r[0].y}, {r[0].z, r[0].w}, {r[1].x, r[1].y}, {r[1].z, r[1].w},
-                                  {r[2].x, r[2].y}, {r[2].z, r[2].w}, {r[3].x, r[3].y}, {r[3].z, r[3].w}};
+    for (int i = 0; i < NCH; ++i) {
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(base + i * rowstep + voff);
+        r[i] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+}
+template <typename T, int NCH>
+__device__ __forceinline__ void gload_rowfast_fast(uint4 (&r)[NCH], const char* base, long long kstep, uint32_t voff) {
+    constexpr int VEC = Vec<T>::N;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t w[4];
+    for (int pass = 0; pass < NCH / 4; ++pass) {
+        const char* pb = base + pass * 128 * (int)sizeof(T) + voff;
+        if (sizeof(T) == 4) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                uint32_t lo = L[2 * q][j >> 1], hi = L[2 * q + 1][j >> 1];
-                // pick the 16-bit half (j & 1) of both words: result = half(lo) | half(hi) << 16
-                w[q] = (j & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
-                               : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            for (int i = 0; i < 4; ++i) {
+                const u32x4_t v = *reinterpret_cast<const u32x4_t*>(pb + i * kstep);
+                r[pass * 4 + i] = make_uint4(v[0], v[1], v[2], v[3]);
             }
-            int row = rq * 4 + j;
-            s[row * CHUNKS + (kc ^ swz(row))] = make_uint4(w[0], w[1], w[2], w[3]);
+        } else {
+            u32x2_t w[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) w[i] = *reinterpret_cast<const u32x2_t*>(pb + i * kstep);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[pass * 4 + q] = make_uint4(w[2 * q][0], w[2 * q][1], w[2 * q + 1][0], w[2 * q + 1][1]);
+        }
+    }
+}
+
+// LDS stores through offsets computed once per thread (uint4 units): soff for the K-fast form,
+// soffj[j] for row j of the four-row group of the row-fast form.
+template <int NCH>
+__device__ __forceinline__ void sstore_kfast_off(uint4* s, const uint4 (&r)[NCH], int soff) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) s[soff + i * 32 * CHUNKS] = r[i];
+}
+template <typename T, int NCH>
+__device__ __forceinline__ void sstore_rowfast_off(uint4* s, const uint4 (&r)[NCH], const int (&soffj)[4]) {
+#pragma unroll
+    for (int pass = 0; pass < NCH / 4; ++pass) {
+        const uint4* rp = &r[pass * 4];
+        if (sizeof(T) == 4) {
+            const uint32_t a[4][4] = {{rp[0].x, rp[0].y, rp[0].z, rp[0].w}, {rp[1].x, rp[1].y, rp[1].z, rp[1].w},
+                                      {rp[2].x, rp[2].y, rp[2].z, rp[2].w}, {rp[3].x, rp[3].y, rp[3].z, rp[3].w}};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s[soffj[j] + pass * 128 * CHUNKS] = make_uint4(a[0][j], a[1][j], a[2][j], a[3][j]);
+        } else {
+            const uint32_t L[8][2] = {{rp[0].x, rp[0].y}, {rp[0].z, rp[0].w}, {rp[1].x, rp[1].y}, {rp[1].z, rp[1].w},
+                                      {rp[2].x, rp[2].y}, {rp[2].z, rp[2].w}, {rp[3].x, rp[3].y}, {rp[3].z, rp[3].w}};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t w[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t lo = L[2 * q][j >> 1], hi = L[2 * q + 1][j >> 1];
+                    w[q] = (j & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                }
+                s[soffj[j] + pass * 128 * CHUNKS] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
         }
     }
 }
@@ -179,12 +216,14 @@ __device__ __forceinline__ void mma(f32x16_t& acc, const uint4& a, const uint4& 
     }
 }
 
-template <typename TI, typename TO, bool AT, bool BT>
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, bool FAST, bool RS>
 __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
     constexpr int VEC = Vec<TI>::N;
     constexpr int BK = CHUNKS * VEC;
-    __shared__ uint4 sA[2][BM * CHUNKS];
-    __shared__ uint4 sB[2][BN * CHUNKS];
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int NCA = BM / 32, NCB = BN / 32;         // 16-byte chunks staged per thread and slab
+    extern __shared__ uint4 smem[];                     // [2][(BM + BN) * CHUNKS]
+    constexpr int STAGE = (BM + BN) * CHUNKS;           // 16-byte words per buffer: A rows, then B rows
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -206,21 +245,25 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
     const int tn = (lin % band) / bh;
     const int row0 = tm * BM, col0 = tn * BN;
     const int z = blockIdx.z;
+    const int split = blockIdx.y;
 
-    f32x16_t acc[2][2];
+    f32x16_t acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     // Row sums of A ride along as one more product against a fragment of ones; only the
     // workgroups of the first tile column, and in them the waves of the first half, do it.
-    const bool do_rs = P.rowsum != nullptr && tn == 0 && wn == 0;
-    f32x16_t rs[2];
+    // (RS is instantiated for the 128x128 shape with both operands transposed only: the
+    // weight-gradient products are the ones that need row sums.)
+    constexpr int NRS = RS ? TM : 1;
+    const bool do_rs = RS && P.rowsum != nullptr && tn == 0 && wn == 0;
+    f32x16_t rs[NRS];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NRS; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) rs[i][e] = 0.0f;
     const uint32_t one_w = sizeof(TI) == 2 ? 0x3F803F80u : 0x3F800000u;
@@ -229,89 +272,151 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
     int ntiles[2];
     ntiles[0] = (P.K[0] + BK - 1) / BK;
     ntiles[1] = P.nseg > 1 ? (P.K[1] + BK - 1) / BK : 0;
-    const int total = ntiles[0] + ntiles[1];
-
-    Operand opA[2], opB[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        opA[s] = P.A[s]; opB[s] = P.B[s];
-        opA[s].p = static_cast<const TI*>(P.A[s].p) + z * P.sA[s];
-        opB[s].p = static_cast<const TI*>(P.B[s].p) + z * P.sB[s];
+    int it_begin = 0, it_end = ntiles[0] + ntiles[1];
+    if (P.splits > 1) {                                  // slabs [it_begin, it_end) of this split (one segment only)
+        const int per = (ntiles[0] + P.splits - 1) / P.splits;
+        it_begin = split * per;
+        it_end = min(ntiles[0], it_begin + per);
+        if (it_end < it_begin) it_end = it_begin;
     }
 
-    uint4 ra[4], rb[4];
+    // Segment operands as scalars selected per slab (indexing an array of structs at run time
+    // would put it in scratch memory).
+    Operand a0 = P.A[0], a1 = P.A[1], b0 = P.B[0], b1 = P.B[1];
+    a0.p = static_cast<const TI*>(P.A[0].p) + z * P.sA[0];
+    a1.p = static_cast<const TI*>(P.A[1].p) + z * P.sA[1];
+    b0.p = static_cast<const TI*>(P.B[0].p) + z * P.sB[0];
+    b1.p = static_cast<const TI*>(P.B[1].p) + z * P.sB[1];
+    const int K0 = P.K[0], K1 = P.K[1];
+
+    // per-thread LDS offsets (uint4 units), computed once
+    const int soff_k = (tid >> 3) * CHUNKS + ((tid & 7) ^ swz(tid >> 3));
+    int soff_r[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { const int r = (tid & 31) * 4 + j; soff_r[j] = r * CHUNKS + ((tid >> 5) ^ swz(r)); }
+    const int arow = wm * (32 * TM) + (lane & 31);
+    const int brow = wn * (32 * TN) + (lane & 31);
+    int roff_a[CHUNKS / 2], roff_b[CHUNKS / 2];
+#pragma unroll
+    for (int q = 0; q < CHUNKS / 2; ++q) {
+        roff_a[q] = arow * CHUNKS + ((2 * q + (lane >> 5)) ^ swz(arow));
+        roff_b[q] = brow * CHUNKS + ((2 * q + (lane >> 5)) ^ swz(brow));
+    }
+    // per-thread global byte offsets of the unguarded loads
+    constexpr int ES = (int)sizeof(TI);
+    const uint32_t voff_a = AT ? (uint32_t)((tid >> 5) * VEC * a0.ld * ES + (tid & 31) * 4 * ES)
+                               : (uint32_t)((tid >> 3) * a0.ld * ES + (tid & 7) * 16);
+    const uint32_t voff_b = BT ? (uint32_t)((tid >> 5) * VEC * b0.ld * ES + (tid & 31) * 4 * ES)
+                               : (uint32_t)((tid >> 3) * b0.ld * ES + (tid & 7) * 16);
+
+    uint4 ra[NCA], rb[NCB];
     auto gload = [&](int it) {
-        const int s = (it >= ntiles[0]) ? 1 : 0;
+        const bool s = it >= ntiles[0];
         const int k0 = (it - (s ? ntiles[0] : 0)) * BK;
-        if (AT) gload_rowfast<TI>(ra, opA[s], row0, P.K[s], k0, tid);
-        else    gload_kfast<TI>(ra, opA[s], row0, P.K[s], k0, tid);
-        if (BT) gload_rowfast<TI>(rb, opB[s], col0, P.K[s], k0, tid);
-        else    gload_kfast<TI>(rb, opB[s], col0, P.K[s], k0, tid);
+        Operand oa, ob;
+        oa.p = s ? a1.p : a0.p; oa.ld = s ? a1.ld : a0.ld; oa.rows = a0.rows; oa.fast = s ? a1.fast : a0.fast;
+        ob.p = s ? b1.p : b0.p; ob.ld = s ? b1.ld : b0.ld; ob.rows = b0.rows; ob.fast = s ? b1.fast : b0.fast;
+        if constexpr (FAST) {
+            // (both segments of a two-segment product share their leading dimensions in this mode)
+            const char* pa = static_cast<const char*>(oa.p);
+            const char* pb = static_cast<const char*>(ob.p);
+            if constexpr (AT) gload_rowfast_fast<TI, NCA>(ra, pa + ((long long)k0 * oa.ld + row0) * ES, oa.ld * ES, voff_a);
+            else    gload_kfast_fast<TI, NCA>(ra, pa + ((long long)row0 * oa.ld + k0) * ES, 32 * oa.ld * ES, voff_a);
+            if constexpr (BT) gload_rowfast_fast<TI, NCB>(rb, pb + ((long long)k0 * ob.ld + col0) * ES, ob.ld * ES, voff_b);
+            else    gload_kfast_fast<TI, NCB>(rb, pb + ((long long)col0 * ob.ld + k0) * ES, 32 * ob.ld * ES, voff_b);
+        } else {
+            const int K = s ? K1 : K0;
+            if constexpr (AT) gload_rowfast<TI, NCA>(ra, oa, row0, K, k0, tid);
+            else              gload_kfast<TI, NCA>(ra, oa, row0, K, k0, tid);
+            if constexpr (BT) gload_rowfast<TI, NCB>(rb, ob, col0, K, k0, tid);
+            else              gload_kfast<TI, NCB>(rb, ob, col0, K, k0, tid);
+        }
     };
     auto sstore = [&](int buf) {
-        if (AT) sstore_rowfast<TI>(sA[buf], ra, tid); else sstore_kfast(sA[buf], ra, tid);
-        if (BT) sstore_rowfast<TI>(sB[buf], rb, tid); else sstore_kfast(sB[buf], rb, tid);
+        uint4* a_s = smem + buf * STAGE;
+        uint4* b_s = a_s + BM * CHUNKS;
+        if constexpr (AT) sstore_rowfast_off<TI, NCA>(a_s, ra, soff_r); else sstore_kfast_off<NCA>(a_s, ra, soff_k);
+        if constexpr (BT) sstore_rowfast_off<TI, NCB>(b_s, rb, soff_r); else sstore_kfast_off<NCB>(b_s, rb, soff_k);
+    };
+    auto lfrag = [&](const uint4* a_s, const uint4* b_s, int q, uint4 (&af)[TM], uint4 (&bf)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = a_s[roff_a[q] + i * 32 * CHUNKS];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bf[j] = b_s[roff_b[q] + j * 32 * CHUNKS];
     };
 
-    if (total > 0) {
-        gload(0);
+    if (it_end > it_begin) {
+        gload(it_begin);
         sstore(0);
     }
     __syncthreads();
-    for (int it = 0; it < total; ++it) {
-        const int buf = it & 1;
-        if (it + 1 < total) gload(it + 1);
-        const uint4* a_s = sA[buf];
-        const uint4* b_s = sB[buf];
+    for (int it = it_begin; it < it_end; ++it) {
+        const int buf = (it - it_begin) & 1;
+        if (it + 1 < it_end) gload(it + 1);
+        const uint4* a_s = smem + buf * STAGE;
+        const uint4* b_s = a_s + BM * CHUNKS;
+        // the small tile keeps two sets of fragments in flight; the large one has no registers to spare
+        constexpr int NF = (TM * TN <= 4) ? 2 : 1;
+        uint4 af[NF][TM], bf[NF][TN];
+        if (NF == 2) lfrag(a_s, b_s, 0, af[0], bf[0]);
 #pragma unroll
         for (int q = 0; q < CHUNKS / 2; ++q) {
-            const int kc = 2 * q + (lane >> 5);
-            uint4 af[2], bfr[2];
+            if (NF == 2) { if (q + 1 < CHUNKS / 2) lfrag(a_s, b_s, q + 1, af[(q + 1) % NF], bf[(q + 1) % NF]); }
+            else lfrag(a_s, b_s, q, af[0], bf[0]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                int ar = wm * 64 + i * 32 + (lane & 31);
-                af[i] = a_s[ar * CHUNKS + (kc ^ swz(ar))];
-                int br = wn * 64 + i * 32 + (lane & 31);
-                bfr[i] = b_s[br * CHUNKS + (kc ^ swz(br))];
-            }
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int j = 0; j < TN; ++j) mma<TI>(acc[i][j], af[q % NF][i], bf[q % NF][j]);
+            if (RS && do_rs && it < ntiles[0]) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) mma<TI>(acc[i][j], af[i], bfr[j]);
-            if (do_rs && it < ntiles[0]) {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) mma<TI>(rs[i], af[i], ones);
+                for (int i = 0; i < NRS; ++i) mma<TI>(rs[i], af[q % NF][i], ones);
             }
         }
-        if (it + 1 < total) sstore(buf ^ 1);
+        if (it + 1 < it_end) sstore(buf ^ 1);
         __syncthreads();
     }
 
-    if (do_rs && (lane & 31) == 0) {
-        float* out = P.rowsum + z * P.sRowsum;
+    if (RS && do_rs && (lane & 31) == 0) {
+        float* out = P.splits > 1 ? P.rs_partial + ((long long)z * P.splits + split) * P.M : P.rowsum + z * P.sRowsum;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NRS; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const int row = row0 + wm * (32 * TM) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
                 if (row < P.M) out[row] = rs[i][e];
             }
     }
 
     // Epilogue: accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32.
+    if (P.splits > 1) {
+        float* part = P.partial + ((long long)z * P.splits + split) * (long long)P.M * P.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = col0 + wn * (32 * TN) + j * 32 + (lane & 31);
+                if (col >= P.N) continue;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = row0 + wm * (32 * TM) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                    if (row < P.M) part[(long long)row * P.N + col] = acc[i][j][e];
+                }
+            }
+        return;
+    }
     TO* C = static_cast<TO*>(P.C) + z * P.sC;
     const TI* bias = P.bias ? static_cast<const TI*>(P.bias) + z * P.sBias : nullptr;
     const float* add = P.add ? P.add + z * P.sAdd : nullptr;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int col = col0 + wn * 64 + j * 32 + (lane & 31);
+        for (int j = 0; j < TN; ++j) {
+            const int col = col0 + wn * (32 * TN) + j * 32 + (lane & 31);
             if (col >= P.N) continue;
             const float bv = bias ? ld_f(bias + col) : 0.0f;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = row0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const int row = row0 + wm * (32 * TM) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
                 if (row < P.M) {
                     float v = acc[i][j][e] + bv;
                     if (add) v += add[(long long)row * P.ldadd + col];
@@ -319,6 +424,33 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
                 }
             }
         }
+}
+
+// C[m][n] = sum over splits of partial[z][s][m][n] (+ bias[n]) in the order s = 0, 1, ...
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N,
+                                                            TO* __restrict__ C, long long ldc, long long sC,
+                                                            const TI* __restrict__ bias, long long sBias,
+                                                            const float* __restrict__ rs_partial, float* __restrict__ rowsum,
+                                                            long long sRowsum) {
+    const int z = blockIdx.z;
+    const long long total = (long long)M * N;
+    if (rowsum)
+        for (long long m = (long long)blockIdx.x * blockDim.x + threadIdx.x; m < M; m += (long long)gridDim.x * blockDim.x) {
+            float v = 0.0f;
+            for (int s = 0; s < splits; ++s) v += rs_partial[((long long)z * splits + s) * M + m];
+            rowsum[z * sRowsum + m] = v;
+        }
+    const float* part = partial + (long long)z * splits * total;
+    TO* Cz = C + z * sC;
+    const TI* bz = bias ? bias + z * sBias : nullptr;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        float v = 0.0f;
+        for (int s = 0; s < splits; ++s) v += part[s * total + i];
+        const int m = (int)(i / N), n = (int)(i % N);
+        if (bz) v += ld_f(bz + n);
+        st_f(&Cz[(long long)m * ldc + n], v);
+    }
 }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -338,6 +470,56 @@ int fast_flags(const void* p, long long ld, long long stride, int batch, bool ro
     return f;
 }
 
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, bool FAST, bool RS>
+hipError_t launch_kernel(const Params& P, dim3 grid, hipStream_t stream) {
+    constexpr size_t lds = 2 * (size_t)(64 * TM + 64 * TN) * CHUNKS * 16;
+    static thread_local bool attr_set = false;
+    if (!attr_set && lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TI, TO, AT, BT, TM, TN, FAST, RS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_kernel<TI, TO, AT, BT, TM, TN, FAST, RS>), grid, dim3(NTHREADS), lds, stream, P);
+    return hipGetLastError();
+}
+
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN>
+hipError_t launch_shape(const Params& P, bool fast, dim3 grid, hipStream_t stream) {
+    if constexpr (AT && BT && TM == 2 && TN == 2) {
+        if (P.rowsum)
+            return fast ? launch_kernel<TI, TO, AT, BT, TM, TN, true, true>(P, grid, stream)
+                        : launch_kernel<TI, TO, AT, BT, TM, TN, false, true>(P, grid, stream);
+    }
+    if (P.rowsum) return hipErrorInvalidValue;           // row sums exist for the dA^T X form on 128x128 tiles only
+    return fast ? launch_kernel<TI, TO, AT, BT, TM, TN, true, false>(P, grid, stream)
+                : launch_kernel<TI, TO, AT, BT, TM, TN, false, false>(P, grid, stream);
+}
+
+template <typename TI, typename TO, int TM, int TN>
+hipError_t launch_form(const GemmDesc& d, const Params& P, bool fast, dim3 grid, hipStream_t stream) {
+    if (!d.atrans && !d.btrans) return launch_shape<TI, TO, false, false, TM, TN>(P, fast, grid, stream);
+    if (!d.atrans && d.btrans) return launch_shape<TI, TO, false, true, TM, TN>(P, fast, grid, stream);
+    if (d.atrans && d.btrans) return launch_shape<TI, TO, true, true, TM, TN>(P, fast, grid, stream);
+    return launch_shape<TI, TO, true, false, TM, TN>(P, fast, grid, stream);
+}
+
+// The unguarded kernel applies when every tile is full, every segment's K is a whole number of
+// slabs, all loads may be of the widest kind, the per-thread offsets fit 32 bits, and the two
+// segments (if any) share their leading dimensions.
+template <typename TI>
+bool can_run_fast(const GemmDesc& d, const Params& P, int tile) {
+    const int bk = CHUNKS * Vec<TI>::N;
+    if (d.M % tile || d.N % tile) return false;
+    for (int s = 0; s < d.nseg; ++s) {
+        if (d.seg[s].K % bk) return false;
+        if (!(P.A[s].fast & 1) || !(P.B[s].fast & 1)) return false;
+        if (d.seg[s].lda != d.seg[0].lda || d.seg[s].ldb != d.seg[0].ldb) return false;
+        if (d.seg[s].lda * (long long)sizeof(TI) * 64 > 0x3FFFFFFF || d.seg[s].ldb * (long long)sizeof(TI) * 64 > 0x3FFFFFFF) return false;
+    }
+    return true;
+}
+
 template <typename TI, typename TO>
 hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     Params P{};
@@ -353,17 +535,60 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     P.add = d.add; P.ldadd = d.ldadd; P.sAdd = d.sAdd;
     P.rowsum = d.rowsum; P.sRowsum = d.sRowsum;
     P.M = d.M; P.N = d.N;
-    P.ntm = (d.M + BM - 1) / BM; P.ntn = (d.N + BN - 1) / BN;
-    dim3 grid((unsigned)(P.ntm * P.ntn), 1, (unsigned)(d.batch > 0 ? d.batch : 1));
-    dim3 block(NTHREADS);
-    if (!d.atrans && !d.btrans) hipLaunchKernelGGL((gemm_kernel<TI, TO, false, false>), grid, block, 0, stream, P);
-    else if (!d.atrans && d.btrans) hipLaunchKernelGGL((gemm_kernel<TI, TO, false, true>), grid, block, 0, stream, P);
-    else if (d.atrans && d.btrans) hipLaunchKernelGGL((gemm_kernel<TI, TO, true, true>), grid, block, 0, stream, P);
-    else hipLaunchKernelGGL((gemm_kernel<TI, TO, true, false>), grid, block, 0, stream, P);
-    return hipGetLastError();
+    const int batch = d.batch > 0 ? d.batch : 1;
+    const GemmPlan plan = plan_gemm(d);
+    const int tile = plan.big_tile ? 256 : 128;
+    P.ntm = (d.M + tile - 1) / tile; P.ntn = (d.N + tile - 1) / tile;
+    P.splits = plan.splits;
+    P.partial = plan.splits > 1 ? d.partial : nullptr;
+    P.rs_partial = plan.splits > 1 ? d.partial + (size_t)plan.splits * batch * d.M * d.N : nullptr;
+    dim3 grid((unsigned)(P.ntm * P.ntn), (unsigned)plan.splits, (unsigned)batch);
+    const bool fast = can_run_fast<TI>(d, P, tile);
+    hipError_t e;
+    if (plan.splits > 1) {
+        // partial tiles are float whatever the output type
+        e = plan.big_tile ? launch_form<TI, float, 4, 4>(d, P, fast, grid, stream) : launch_form<TI, float, 2, 2>(d, P, fast, grid, stream);
+        if (e != hipSuccess) return e;
+        const long long total = (long long)d.M * d.N;
+        unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+        hipLaunchKernelGGL((splitk_reduce_kernel<TI, TO>), dim3(blocks, 1, batch), dim3(256), 0, stream, d.partial, plan.splits,
+                           d.M, d.N, static_cast<TO*>(d.C), d.ldc, d.sC, static_cast<const TI*>(d.bias), d.sBias,
+                           P.rs_partial, d.rowsum, d.sRowsum);
+        return hipGetLastError();
+    }
+    return plan.big_tile ? launch_form<TI, TO, 4, 4>(d, P, fast, grid, stream) : launch_form<TI, TO, 2, 2>(d, P, fast, grid, stream);
 }
 
 }  // namespace
+
+GemmPlan plan_gemm(const GemmDesc& d) {
+    GemmPlan p{false, 1, 0};
+    const int batch = d.batch > 0 ? d.batch : 1;
+    const long long t256 = (long long)((d.M + 255) / 256) * ((d.N + 255) / 256) * batch;
+    const long long t128 = (long long)((d.M + 127) / 128) * ((d.N + 127) / 128) * batch;
+    if (t256 >= 384 && !d.rowsum) { p.big_tile = true; return p; }
+    // few output tiles and a long contraction: split K so that about 256 workgroups are in flight
+    if (d.nseg == 1 && !d.add && d.partial && t128 <= 128) {
+        const int bk = d.in_type == DT_BF16 ? 64 : 32;
+        const int slabs = (d.seg[0].K + bk - 1) / bk;
+        int s = (int)(256 / t128);
+        if (s > 8) s = 8;
+        while (s > 1 && slabs / s < 8) --s;
+        const size_t need = (size_t)s * batch * ((size_t)d.M * d.N + d.M) * sizeof(float);
+        if (s > 1 && need <= d.partial_bytes) {
+            p.splits = s;
+            p.partial_bytes = need;
+        }
+    }
+    return p;
+}
+
+size_t gemm_partial_bytes(int M, int N, int K, int batch, DType in_type) {
+    GemmDesc d{};
+    d.M = M; d.N = N; d.batch = batch; d.nseg = 1; d.seg[0].K = K; d.in_type = in_type;
+    d.partial = reinterpret_cast<float*>(16); d.partial_bytes = ~size_t(0);
+    return plan_gemm(d).partial_bytes;
+}
 
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t stream) {
     if (d.M <= 0 || d.N <= 0) return hipSuccess;

@@ -28,10 +28,22 @@ struct GemmDesc {
     long long ldadd, sAdd;
     float* rowsum;            // rowsum[m] = sum_k A(m,k) of segment 0 (bias gradients), or null
     long long sRowsum;
+    float* partial;           // scratch for split-K partial tiles (float), or null: never split
+    size_t partial_bytes;
     int M, N, batch;
     bool atrans, btrans;
     DType in_type, out_type;  // in_type is the element type of A and B
 };
+
+// How a product is run: 256x256 or 128x128 tiles, and into how many K ranges it is split.
+struct GemmPlan {
+    bool big_tile;
+    int splits;
+    size_t partial_bytes;     // scratch the split needs (0 when splits == 1)
+};
+GemmPlan plan_gemm(const GemmDesc& d);
+// Scratch bytes a product of this shape would use if it were given unlimited scratch.
+size_t gemm_partial_bytes(int M, int N, int K, int batch, DType in_type);
 
 // Validates nothing (the caller's shapes are trusted); returns the launch status.
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t stream);
