@@ -17,6 +17,7 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* sh) {
 }
 
 // One workgroup per row: max, sum of exponentials, loss term, then u <- s (p - onehot) in place.
+// General form: three passes over the row (the second and third normally hit L2).
 template <typename TS>
 __global__ __launch_bounds__(256) void softmax_rows_kernel(TS* u, long long ldu, const int32_t* labels,
                                                            float* row_loss, int V, float s) {
@@ -39,6 +40,65 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(TS* u, long long ldu,
     }
 }
 
+// bf16 rows that fit the registers of one workgroup (V <= 256 * 8 * NC, V a multiple of 8, rows
+// 16-byte aligned): the row is read once with 16-byte loads, kept in registers as packed bf16,
+// reduced, and written back as dE/du with 16-byte stores.  HBM traffic: one read and one write.
+template <int NC>
+__global__ __launch_bounds__(256) void softmax_rows_bf16_regs_kernel(bf16_t* u, long long ldu, const int32_t* labels,
+                                                                      float* row_loss, int V, float s) {
+    __shared__ float sh[4];
+    const int m = blockIdx.x;
+    bf16_t* row = u + (long long)m * ldu;
+    const int nchunks = V >> 3;
+    uint4 r[NC];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        if (c < nchunks) {
+            r[i] = *reinterpret_cast<const uint4*>(row + 8 * c);
+            const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) mx = fmaxf(mx, fmaxf(bf2f((bf16_t)(w[q] & 0xFFFFu)), bf2f((bf16_t)(w[q] >> 16))));
+        } else {
+            r[i] = make_uint4(0, 0, 0, 0);
+        }
+    }
+    mx = block_reduce(mx, true, sh);
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        if (c < nchunks) {
+            const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                sum += __expf(bf2f((bf16_t)(w[q] & 0xFFFFu)) - mx) + __expf(bf2f((bf16_t)(w[q] >> 16)) - mx);
+        }
+    }
+    sum = block_reduce(sum, false, sh);
+    const int lab = labels[m];
+    const float inv = 1.0f / sum;
+    if (threadIdx.x == 0) row_loss[m] = s * (logf(sum) + mx - bf2f(row[lab]));
+    __syncthreads();                                   // the label's logit is read before the row is overwritten
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        if (c < nchunks) {
+            const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+            uint32_t o[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int v = 8 * c + 2 * q;
+                const float p0 = __expf(bf2f((bf16_t)(w[q] & 0xFFFFu)) - mx) * inv;
+                const float p1 = __expf(bf2f((bf16_t)(w[q] >> 16)) - mx) * inv;
+                o[q] = pack_bf2(s * (p0 - (v == lab ? 1.0f : 0.0f)), s * (p1 - (v + 1 == lab ? 1.0f : 0.0f)));
+            }
+            *reinterpret_cast<uint4*>(row + 8 * c) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
 __global__ __launch_bounds__(1024) void sum_to_scalar_kernel(const float* v, int M, float* out) {
     __shared__ float sh[16];
     float acc = 0.0f;
@@ -52,8 +112,14 @@ __global__ __launch_bounds__(1024) void sum_to_scalar_kernel(const float* v, int
 hipError_t launch_softmax_rows(void* u, long long ldu, const int32_t* labels, float* row_loss,
                                int M, int V, float s, DType store, hipStream_t st) {
     if (M <= 0) return hipSuccess;
-    if (store == DT_BF16)
-        hipLaunchKernelGGL(softmax_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, st, static_cast<bf16_t*>(u), ldu, labels, row_loss, V, s);
+    if (store == DT_BF16) {
+        bf16_t* ub = static_cast<bf16_t*>(u);
+        const bool vec = (V % 8 == 0) && (ldu % 8 == 0) && (reinterpret_cast<uintptr_t>(u) % 16 == 0);
+        if (vec && V <= 256 * 8 * 4) hipLaunchKernelGGL(softmax_rows_bf16_regs_kernel<4>, dim3(M), dim3(256), 0, st, ub, ldu, labels, row_loss, V, s);
+        else if (vec && V <= 256 * 8 * 8) hipLaunchKernelGGL(softmax_rows_bf16_regs_kernel<8>, dim3(M), dim3(256), 0, st, ub, ldu, labels, row_loss, V, s);
+        else if (vec && V <= 256 * 8 * 16) hipLaunchKernelGGL(softmax_rows_bf16_regs_kernel<16>, dim3(M), dim3(256), 0, st, ub, ldu, labels, row_loss, V, s);
+        else hipLaunchKernelGGL(softmax_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, st, ub, ldu, labels, row_loss, V, s);
+    }
     else
         hipLaunchKernelGGL(softmax_rows_kernel<float>, dim3(M), dim3(256), 0, st, static_cast<float*>(u), ldu, labels, row_loss, V, s);
     return hipGetLastError();
