@@ -7,7 +7,15 @@
 namespace blstm {
 namespace {
 
+// tuning constants (overridable at build time for sweeps)
+#ifndef BLSTM_MIX_UNROLL
+#define BLSTM_MIX_UNROLL 4
+#endif
+#ifndef BLSTM_MIX_BLOCKS
+#define BLSTM_MIX_BLOCKS (256 * 16)
+#endif
 constexpr int UPD_THREADS = 256;
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint2 pack4(float4 v) { return make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)); }
 
@@ -40,31 +48,46 @@ __global__ __launch_bounds__(UPD_THREADS) void sgd_kernel(float* __restrict__ th
     }
 }
 
+// Both members of pair blockIdx.y become their average.  Four independent 16-byte loads per operand
+// are issued before the first store so that enough bytes are in flight to cover HBM latency.
 template <bool SHADOW>
 __global__ __launch_bounds__(UPD_THREADS) void mix_kernel(MixPairs p, size_t n) {
+    constexpr int U = BLSTM_MIX_UNROLL;
     const int pr = blockIdx.y;
-    float* __restrict__ a = p.a[pr];
-    float* __restrict__ b = p.b[pr];
+    f32x4_t* __restrict__ a = reinterpret_cast<f32x4_t*>(p.a[pr]);
+    f32x4_t* __restrict__ b = reinterpret_cast<f32x4_t*>(p.b[pr]);
+    u32x2_t* __restrict__ sa = reinterpret_cast<u32x2_t*>(p.sa[pr]);
+    u32x2_t* __restrict__ sb = reinterpret_cast<u32x2_t*>(p.sb[pr]);
     const size_t n4 = n / 4;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        const float4 x = reinterpret_cast<const float4*>(a)[i];
-        const float4 y = reinterpret_cast<const float4*>(b)[i];
-        float4 m;
-        m.x = 0.5f * (x.x + y.x); m.y = 0.5f * (x.y + y.y); m.z = 0.5f * (x.z + y.z); m.w = 0.5f * (x.w + y.w);
-        reinterpret_cast<float4*>(a)[i] = m;
-        reinterpret_cast<float4*>(b)[i] = m;
-        if (SHADOW) {
-            const uint2 s = pack4(m);
-            reinterpret_cast<uint2*>(p.sa[pr])[i] = s;
-            reinterpret_cast<uint2*>(p.sb[pr])[i] = s;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + (U - 1) * stride < n4; i += U * stride) {
+        f32x4_t x[U], y[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) { x[k] = __builtin_nontemporal_load(a + i + k * stride); y[k] = __builtin_nontemporal_load(b + i + k * stride); }
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const f32x4_t m = 0.5f * (x[k] + y[k]);
+            __builtin_nontemporal_store(m, a + i + k * stride);
+            __builtin_nontemporal_store(m, b + i + k * stride);
+            if (SHADOW) {
+                u32x2_t s; s[0] = pack_bf2(m[0], m[1]); s[1] = pack_bf2(m[2], m[3]);
+                __builtin_nontemporal_store(s, sa + i + k * stride);
+                __builtin_nontemporal_store(s, sb + i + k * stride);
+            }
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
-        const size_t i = n4 * 4 + threadIdx.x;
-        const float m = 0.5f * (a[i] + b[i]);
+    for (; i < n4; i += stride) {
+        const f32x4_t m = 0.5f * (a[i] + b[i]);
         a[i] = m; b[i] = m;
-        if (SHADOW) { p.sa[pr][i] = f2bf(m); p.sb[pr][i] = f2bf(m); }
+        if (SHADOW) { u32x2_t s; s[0] = pack_bf2(m[0], m[1]); s[1] = pack_bf2(m[2], m[3]); sa[i] = s; sb[i] = s; }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const size_t j = n4 * 4 + threadIdx.x;
+        float* fa = p.a[pr]; float* fb = p.b[pr];
+        const float m = 0.5f * (fa[j] + fb[j]);
+        fa[j] = m; fb[j] = m;
+        if (SHADOW) { p.sa[pr][j] = f2bf(m); p.sb[pr][j] = f2bf(m); }
     }
 }
 
@@ -101,7 +124,7 @@ hipError_t launch_sgd(float* theta, unsigned short* shadow, const float* grad, s
 
 hipError_t launch_mix(const MixPairs& p, size_t n, hipStream_t st) {
     if (n == 0 || p.npairs == 0) return hipSuccess;
-    unsigned per_pair = blocks_for(n / 4, (256 * 16 + p.npairs - 1) / p.npairs);
+    unsigned per_pair = blocks_for(n / 4, (BLSTM_MIX_BLOCKS + p.npairs - 1) / p.npairs);
     dim3 grid(per_pair, (unsigned)p.npairs), block(UPD_THREADS);
     if (p.sa[0]) hipLaunchKernelGGL(mix_kernel<true>, grid, block, 0, st, p, n);
     else hipLaunchKernelGGL(mix_kernel<false>, grid, block, 0, st, p, n);
