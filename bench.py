@@ -63,6 +63,7 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel-class event pass")
     ap.add_argument("--rec-sync", type=int, default=-1, help="exchange protocol of the persistent kernels (library default if < 0)")
     ap.add_argument("--rec-path", type=int, default=0, help="1 = one launch per frame")
+    ap.add_argument("--overlap", type=int, default=-1, help="0 = weight-gradient products on the caller's stream")
     ap.add_argument("--mix-replicas", type=int, default=16, help="replicas of the separate adpsgd_mix measurement")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -86,6 +87,8 @@ def main():
     lrn = Learner(mode=w.mode, recurrent_path=args.rec_path, **d)
     if args.rec_sync >= 0:
         bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_RECURRENT_SYNC, args.rec_sync)
+    if args.overlap >= 0:
+        bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_OVERLAP, args.overlap)
     theta = inputs.make_theta(lrn.n, w.seed, bf16=bf)
     x, labels = inputs.make_batch(T, B, d["D"], d["V"], w.seed, bf16=bf)
     lrn.set_theta(theta)

@@ -15,7 +15,8 @@
  *   - Every pointer named theta, x, z, dz, grad, labels, loss, velocity or workspace is
  *     DEVICE memory owned by the caller.  The library never allocates or frees
  *     device memory and never synchronises the device: all work is enqueued on the
- *     caller's stream (a hipStream_t passed as void*, NULL = the null stream).
+ *     caller's stream (a hipStream_t passed as void*, NULL = the null stream), or on a
+ *     second stream of the context that is forked from and joined back to it inside a call.
  *   - `partner` and every `*_out` size/offset argument is HOST memory.
  *   - Activations are time-major and row-major: [T][B][features].
  *   - mode 0: every tensor is float.  mode 1: theta, x, z, dz are bfloat16 (the
@@ -120,6 +121,10 @@ int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
    stored write-through and loaded cache-bypassing at agent scope, and a consumer proceeds once
    none of the elements it needs still holds the pattern (each element is its own ready flag). */
 #define BLSTM_OPT_RECURRENT_SYNC 2
+/* BLSTM_OPT_OVERLAP (default 1): blstm_backward runs the weight-gradient products on a second stream
+   owned by the context (default priority), forked from and joined to the caller's stream with events,
+   so that they overlap the next layer's recurrence.  0 keeps everything on the caller's stream. */
+#define BLSTM_OPT_OVERLAP 3
 int blstm_set_option(blstm_ctx* ctx, int option, int value);
 
 /* The only call that synchronises: waits for `stream`, then reports whether a persistent kernel

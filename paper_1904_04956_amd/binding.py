@@ -190,6 +190,7 @@ def blstm_shadow_refresh(theta_master, theta_bf16, n, stream=None):
 
 BLSTM_OPT_RECURRENT_PATH = 1
 BLSTM_OPT_RECURRENT_SYNC = 2
+BLSTM_OPT_OVERLAP = 3
 
 
 def blstm_set_option(ctx, option, value):

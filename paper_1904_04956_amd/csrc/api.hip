@@ -58,11 +58,15 @@ struct blstm_ctx {
     size_t off_wp, off_bp, off_ws, off_bs;
     // workspace (byte offsets)
     std::vector<size_t> wY, wG, wC;
-    size_t wAX, wPRE, wDA, wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, part_bytes, ws_bytes;
+    size_t wAX, wPRE, wDA[2], wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, wPART2, part_bytes, part2_bytes, ws_bytes;
     int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
+    int overlap;              // 1: weight-gradient products run on a second stream beside the next layer's recurrence
+    hipStream_t side;         // created on first use
+    hipEvent_t ev_fork, ev_da[2], ev_wg[2], ev_join;
+    bool side_ready;
     char* ws;
     size_t ws_bound;
     bool have_forward;
@@ -106,12 +110,35 @@ int check_hip(hipError_t e, const char* what) {
         if (e_ != hipSuccess) return check_hip(e_, what);            \
     } while (0)
 
+#define RUN_ON(strm, cls, what, expr)                                \
+    do {                                                             \
+        hipError_t e_;                                               \
+        { Scope sc_(ctx, strm, cls); e_ = (expr); }                  \
+        if (e_ != hipSuccess) return check_hip(e_, what);            \
+    } while (0)
+#define HIPCHK(what, expr)                                           \
+    do { hipError_t e_ = (expr); if (e_ != hipSuccess) return check_hip(e_, what); } while (0)
+
 GemmDesc gemm_desc(const blstm_ctx* c, DType in, DType out) {
     GemmDesc d{};
     d.nseg = 1; d.batch = 1; d.in_type = in; d.out_type = out;
     d.partial = reinterpret_cast<float*>(c->ws + c->wPART);
     d.partial_bytes = c->part_bytes;
     return d;
+}
+
+// The second stream and its events (host objects only), created at the first backward pass that uses them.
+hipError_t ensure_side(blstm_ctx* c) {
+    if (c->side_ready) return hipSuccess;
+    hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+    if (e != hipSuccess) return e;
+    hipEvent_t* evs[6] = {&c->ev_fork, &c->ev_join, &c->ev_da[0], &c->ev_da[1], &c->ev_wg[0], &c->ev_wg[1]};
+    for (hipEvent_t* ev : evs) {
+        e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
+        if (e != hipSuccess) return e;
+    }
+    c->side_ready = true;
+    return hipSuccess;
 }
 
 inline const char* at(const void* base, size_t elems, size_t esz) { return static_cast<const char*>(base) + elems * esz; }
@@ -165,7 +192,8 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     }
     c->wAX = w;      w += up256(M * 8 * H * 4);
     c->wPRE = w;     w += up256(2 * B * 4 * H * 4);
-    c->wDA = w;      w += up256(M * 8 * H * e);
+    c->wDA[0] = w;   w += up256(M * 8 * H * e);
+    c->wDA[1] = w;   w += up256(M * 8 * H * e);
     c->wDY[0] = w;   w += up256(M * 2 * H * e);
     c->wDY[1] = w;   w += up256(M * 2 * H * e);
     c->wDH = w;      w += up256(2 * B * H * 4);
@@ -197,7 +225,15 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
         upd(c->B, c->H, 4 * c->H, 2);                             // recurrent gradient of the step-by-step path
         c->wPART = w; c->part_bytes = up256(need);
         w += c->part_bytes;
+        // a second scratch for the weight-gradient products that run on the second stream
+        size_t need2 = 0;
+        auto upd2 = [&](int m, int n, int k, int batch) { size_t b = gemm_partial_bytes(m, n, k, batch, S); if (b > need2) need2 = b; };
+        if (c->P > 0) upd2(c->P, 2 * c->H, c->M, 1);
+        for (int l = 0; l < c->L; ++l) { upd2(4 * c->H, c->din(l), c->M, 2); upd2(4 * c->H, c->H, (c->T - 1) * c->B, 2); }
+        c->wPART2 = w; c->part2_bytes = up256(need2);
+        w += c->part2_bytes;
     }
+    c->overlap = 1; c->side = nullptr; c->side_ready = false;
     c->ws_bytes = w;
     c->ws = nullptr; c->ws_bound = 0; c->have_forward = false;
     c->prof = false; c->recs_used = 0;
@@ -209,6 +245,11 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
 
 void blstm_destroy(blstm_ctx* c) {
     if (!c) return;
+    if (c->side_ready) {
+        (void)hipStreamDestroy(c->side);
+        (void)hipEventDestroy(c->ev_fork); (void)hipEventDestroy(c->ev_join);
+        for (int i = 0; i < 2; ++i) { (void)hipEventDestroy(c->ev_da[i]); (void)hipEventDestroy(c->ev_wg[i]); }
+    }
     for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete c;
 }
@@ -385,20 +426,37 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
     const int T = ctx->T, B = ctx->B, H = ctx->H, M = ctx->M, P = ctx->P;
     const size_t e = ctx->esz;
     const DType S = ctx->st;
-    char* DA = ctx->ws + ctx->wDA;
     float* DH = reinterpret_cast<float*>(ctx->ws + ctx->wDH);
     float* DC = reinterpret_cast<float*>(ctx->ws + ctx->wDC);
+    // Weight-gradient products only feed the gradient vector, so they run on a second stream beside
+    // the next layer's (latency-bound) recurrence: fork after each layer's dE/da is complete, join at
+    // the end.  dE/da alternates between two buffers so that a layer's products can still read theirs
+    // while the next layer writes the other.
+    const bool ov = ctx->overlap != 0;
+    hipStream_t ws = st;                                 // stream of the weight-gradient products
+    if (ov) {
+        HIPCHK("second stream", ensure_side(ctx));
+        ws = ctx->side;
+        HIPCHK("fork", hipEventRecord(ctx->ev_fork, st));
+        HIPCHK("fork", hipStreamWaitEvent(ws, ctx->ev_fork, 0));
+    }
+    auto wgrad_desc = [&](DType out) {
+        GemmDesc d = gemm_desc(ctx, S, out);
+        if (ov) { d.partial = reinterpret_cast<float*>(ctx->ws + ctx->wPART2); d.partial_bytes = ctx->part2_bytes; }
+        return d;
+    };
+    bool wg_pending[2] = {false, false};
     const char* dY;
     int next_buf = 0;
     if (P > 0) {
         const char* YL = ctx->ws + ctx->wY[ctx->L - 1];
         {   // dW_p = dz^T y
-            GemmDesc d = gemm_desc(ctx, S, DT_F32);
+            GemmDesc d = wgrad_desc(DT_F32);
             d.M = P; d.N = 2 * H; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{dz, YL, P, 2 * H, 0, 0, M};
             d.C = grad + ctx->off_wp; d.ldc = 2 * H;
             d.rowsum = grad + ctx->off_bp;             // db_p = sum over frames of dz
-            RUN(PC_GEMM_WGRAD, "dW_p", launch_gemm(d, st));
+            RUN_ON(ws, PC_GEMM_WGRAD, "dW_p", launch_gemm(d, ws));
         }
         {   // dy = dz W_p
             GemmDesc d = gemm_desc(ctx, S, S);
@@ -418,6 +476,12 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
         const char* Y = ctx->ws + ctx->wY[l];
         const char* G = ctx->ws + ctx->wG[l];
         const float* C = reinterpret_cast<const float*>(ctx->ws + ctx->wC[l]);
+        const int db = l & 1;
+        char* DA = ctx->ws + ctx->wDA[db];
+        if (ov && wg_pending[db]) {                      // the products of layer l+2 still read this buffer
+            HIPCHK("buffer reuse", hipStreamWaitEvent(st, ctx->ev_wg[db], 0));
+            wg_pending[db] = false;
+        }
         bool rec_done = false;
         if (ctx->rec_nbg > 0 && ctx->rec_path == 0) {
             unsigned* cnt = reinterpret_cast<unsigned*>(ctx->ws + ctx->wCNT);
@@ -464,17 +528,21 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
                 RUN(PC_GEMM_REC_BWD, "recurrent gradient", launch_gemm(d, st));
             }
         }
+        if (ov) {                                        // dE/da of this layer is complete: fork
+            HIPCHK("fork", hipEventRecord(ctx->ev_da[db], st));
+            HIPCHK("fork", hipStreamWaitEvent(ws, ctx->ev_da[db], 0));
+        }
         {   // dW_x = da^T x, both directions
-            GemmDesc d = gemm_desc(ctx, S, DT_F32);
+            GemmDesc d = wgrad_desc(DT_F32);
             d.batch = 2; d.M = 4 * H; d.N = Din; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{DA, Xin, 8 * H, Din, 4 * H, 0, M};
             d.C = grad + ctx->off_wx[0][l]; d.ldc = Din; d.sC = (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]);
             d.rowsum = grad + ctx->off_b[0][l];        // db = sum over frames of da
             d.sRowsum = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);
-            RUN(PC_GEMM_WGRAD, "dW_x", launch_gemm(d, st));
+            RUN_ON(ws, PC_GEMM_WGRAD, "dW_x", launch_gemm(d, ws));
         }
         {   // dU_h = da^T h_prev: forward direction pairs da[t] with h[t-1], backward direction with h[t+1]
-            GemmDesc d = gemm_desc(ctx, S, DT_F32);
+            GemmDesc d = wgrad_desc(DT_F32);
             d.batch = 2; d.M = 4 * H; d.N = H; d.atrans = true; d.btrans = true;
             const char* A0 = DA + ((size_t)B * 8 * H) * e;
             const char* A1 = DA + ((size_t)4 * H) * e;
@@ -482,7 +550,11 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             const char* B1 = Y + ((size_t)B * 2 * H + H) * e;
             d.seg[0] = GemmSeg{A0, B0, 8 * H, 2 * H, (long long)((A1 - A0) / (long long)e), (long long)((B1 - B0) / (long long)e), (T - 1) * B};
             d.C = grad + ctx->off_uh[0][l]; d.ldc = H; d.sC = (long long)(ctx->off_uh[1][l] - ctx->off_uh[0][l]);
-            RUN(PC_GEMM_WGRAD, "dU_h", launch_gemm(d, st));
+            RUN_ON(ws, PC_GEMM_WGRAD, "dU_h", launch_gemm(d, ws));
+        }
+        if (ov) {
+            HIPCHK("fork", hipEventRecord(ctx->ev_wg[db], ws));
+            wg_pending[db] = true;
         }
         if (l > 0) {   // dx = da_fwd W_x_fwd + da_bwd W_x_bwd, the gradient of the layer below's output
             GemmDesc d = gemm_desc(ctx, S, S);
@@ -494,6 +566,10 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             dY = ctx->ws + ctx->wDY[next_buf];
             next_buf ^= 1;
         }
+    }
+    if (ov) {                                            // join: everything on the second stream precedes what follows on st
+        HIPCHK("join", hipEventRecord(ctx->ev_join, ws));
+        HIPCHK("join", hipStreamWaitEvent(st, ctx->ev_join, 0));
     }
     return BLSTM_OK;
 }
@@ -552,6 +628,7 @@ int blstm_set_option(blstm_ctx* c, int option, int value) {
     if (!c) return fail(BLSTM_ERR_NULL, "blstm_set_option: null argument");
     if (option == BLSTM_OPT_RECURRENT_PATH && (value == 0 || value == 1)) { c->rec_path = value; return BLSTM_OK; }
     if (option == BLSTM_OPT_RECURRENT_SYNC && (value == 0 || value == 1)) { c->rec_sync = value; return BLSTM_OK; }
+    if (option == BLSTM_OPT_OVERLAP && (value == 0 || value == 1)) { c->overlap = value; return BLSTM_OK; }
     return fail(BLSTM_ERR_DIM, "blstm_set_option: unknown option %d or value %d", option, value);
 }
 

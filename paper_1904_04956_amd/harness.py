@@ -16,7 +16,7 @@ from . import inputs
 class Learner:
     """Buffers of one learner: master weights, bf16 shadow, gradient, batch, workspace."""
 
-    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0, recurrent_path=0, recurrent_sync=None):
+    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0, recurrent_path=0, recurrent_sync=None, overlap=None):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the HIP path has no CPU fallback")
         self.dims = dict(T=T, B=B, D=D, H=H, L=L, P=P, V=V)
@@ -25,6 +25,8 @@ class Learner:
         self.ctx = bl.blstm_create(T, B, D, H, L, P, V, mode, loss_scale)
         if recurrent_path:
             bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_RECURRENT_PATH, recurrent_path)
+        if overlap is not None:
+            bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_OVERLAP, int(overlap))
         if recurrent_sync is not None:
             bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_RECURRENT_SYNC, recurrent_sync)
         self.n = bl.blstm_param_count(self.ctx)
