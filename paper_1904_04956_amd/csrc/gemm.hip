@@ -50,6 +50,7 @@ struct Params {
     float* partial;                 // split-K: float [batch][splits][M][N], or null
     float* rs_partial;              // split-K: float [batch][splits][M] row sums
     int M, N, ntm, ntn, splits;
+    int c_vec;                      // C rows may be written with 16-byte (float) / 8-byte (bf16) stores
     long long sA[2], sB[2], sC, sBias, sAdd, sRowsum;
 };
 
@@ -407,6 +408,40 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
     TO* C = static_cast<TO*>(P.C) + z * P.sC;
     const TI* bias = P.bias ? static_cast<const TI*>(P.bias) + z * P.sBias : nullptr;
     const float* add = P.add ? P.add + z * P.sAdd : nullptr;
+    if constexpr (FAST && TM == 2 && TN == 2) {
+        // Full 128x128 tile: stage it through LDS (free after the loop's last barrier) so that every
+        // store instruction writes whole rows of the tile, 16 bytes (float) or 8 bytes (bf16) per lane.
+        // 16-byte column groups are XOR-swizzled with the row so both sides spread over the banks.
+        if (sizeof(TO) == 2 && P.c_vec && !add) {   // (float rows already leave as full 128-byte segments)
+            float* cs = reinterpret_cast<float*>(smem);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = wn * 64 + j * 32 + (lane & 31);
+                const float bv = bias ? ld_f(bias + col0 + col) : 0.0f;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int row = wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                        cs[row * 128 + ((((col >> 2) ^ (row & 7))) << 2) + (col & 3)] = acc[i][j][e] + bv;
+                    }
+            }
+            __syncthreads();
+            const int g = tid & 31;
+#pragma unroll 4
+            for (int pass = 0; pass < 16; ++pass) {
+                const int r = pass * 8 + (tid >> 5);
+                const float4 v = *reinterpret_cast<const float4*>(&cs[r * 128 + ((g ^ (r & 7)) << 2)]);
+                TO* dst = C + (long long)(row0 + r) * P.ldc + col0 + 4 * g;
+                if constexpr (sizeof(TO) == 4) {
+                    *reinterpret_cast<float4*>(dst) = v;
+                } else {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w));
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -535,6 +570,10 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     P.add = d.add; P.ldadd = d.ldadd; P.sAdd = d.sAdd;
     P.rowsum = d.rowsum; P.sRowsum = d.sRowsum;
     P.M = d.M; P.N = d.N;
+    {
+        const size_t w = sizeof(TO) == 4 ? 16 : 8;
+        P.c_vec = aligned(d.C, w) && d.ldc % 4 == 0 && ((d.batch > 1 ? d.sC : 0) % 4 == 0);
+    }
     const int batch = d.batch > 0 ? d.batch : 1;
     const GemmPlan plan = plan_gemm(d);
     const int tile = plan.big_tile ? 256 : 128;
@@ -566,7 +605,11 @@ GemmPlan plan_gemm(const GemmDesc& d) {
     const int batch = d.batch > 0 ? d.batch : 1;
     const long long t256 = (long long)((d.M + 255) / 256) * ((d.N + 255) / 256) * batch;
     const long long t128 = (long long)((d.M + 127) / 128) * ((d.N + 127) / 128) * batch;
-    if (t256 >= 384 && !d.rowsum) { p.big_tile = true; return p; }
+    // the large tile has one workgroup per CU, so its prologue and epilogue are exposed: it pays only
+    // when the contraction is long enough to amortise them
+    int ktot = 0;
+    for (int s = 0; s < d.nseg; ++s) ktot += d.seg[s].K;
+    if (t256 >= 1024 && !d.rowsum && ktot >= 512) { p.big_tile = true; return p; }
     // few output tiles and a long contraction: split K so that about 256 workgroups are in flight
     if (d.nseg == 1 && !d.add && d.partial && t128 <= 128) {
         const int bk = d.in_type == DT_BF16 ? 64 : 32;
