@@ -58,7 +58,7 @@ struct blstm_ctx {
     size_t off_wp, off_bp, off_ws, off_bs;
     // workspace (byte offsets)
     std::vector<size_t> wY, wG, wC;
-    size_t wAX, wPRE, wDA[2], wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, wPART2, part_bytes, part2_bytes, ws_bytes;
+    size_t wAX, wPRE, wDA[2], wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, wPART2, wYend, part_bytes, part2_bytes, ws_bytes;
     int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
@@ -185,8 +185,9 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     // workspace layout
     const size_t M = (size_t)c->M, B = (size_t)c->B, e = c->esz;
     size_t w = 0;
+    for (int l = 0; l < c->L; ++l) { c->wY.push_back(w); w += up256(M * 2 * H * e); }   // contiguous: one fill covers all
+    c->wYend = w;
     for (int l = 0; l < c->L; ++l) {
-        c->wY.push_back(w); w += up256(M * 2 * H * e);
         c->wG.push_back(w); w += up256(M * 8 * H * e);
         c->wC.push_back(w); w += up256(M * 2 * H * 4);
     }
@@ -298,6 +299,9 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
     float* AX = reinterpret_cast<float*>(ctx->ws + ctx->wAX);
     float* PRE = reinterpret_cast<float*>(ctx->ws + ctx->wPRE);
     ctx->have_forward = false;
+    const bool persistent = ctx->rec_nbg > 0 && ctx->rec_path == 0;
+    if (persistent && ctx->rec_sync == 1)    // h of every layer starts as "not written yet"
+        RUN(PC_MISC, "sentinel fill of h", launch_fill_bytes16(ctx->ws + ctx->wY[0], ctx->wYend - ctx->wY[0], 0xFFFFFFFFu, st));
     for (int l = 0; l < ctx->L; ++l) {
         const void* Xin = l == 0 ? x : static_cast<const void*>(ctx->ws + ctx->wY[l - 1]);
         const int Din = ctx->din(l);
@@ -320,14 +324,13 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
                 RUN(PC_MISC, "abort word", launch_fill_u32(cnt + ncnt, 1, 0u, st));
                 ctx->abort_clean = true;
             }
-            RUN(PC_MISC, "counters", launch_fill_u32(cnt, ncnt, 0u, st));
+            if (ctx->rec_sync == 0) RUN(PC_MISC, "counters", launch_fill_u32(cnt, ncnt, 0u, st));
             RecFwdArgs a{};
             a.uh[0] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[0][l], e));
             a.uh[1] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[1][l], e));
             a.ax = AX; a.y = reinterpret_cast<unsigned short*>(Y); a.gates = reinterpret_cast<unsigned short*>(G); a.c = C;
             a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
-            if (ctx->rec_sync == 1) RUN(PC_MISC, "sentinel fill of h", launch_fill_bytes16(Y, (size_t)M * 2 * H * e, 0xFFFFFFFFu, st));
             bool launched = false;
             RUN(PC_REC_FWD, "persistent recurrent forward", launch_rec_fwd(a, ctx->rec_sync == 1, st, &launched));
             if (launched) continue;
@@ -446,6 +449,28 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
         return d;
     };
     bool wg_pending[2] = {false, false};
+    const bool persistent = ctx->rec_nbg > 0 && ctx->rec_path == 0;
+    const bool sentinel = persistent && ctx->rec_sync == 1;
+    if (persistent) {                                    // U_h^T of every layer and direction in one launch
+        TransposeUhArgs ta{};
+        for (int l = 0; l < ctx->L; ++l)
+            for (int d = 0; d < 2; ++d)
+                ta.src[2 * l + d] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[d][l], e));
+        ta.dst = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wUHT);
+        ta.count = 2 * ctx->L;
+        RUN(PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, st));
+    }
+    // In sentinel mode each dE/da buffer starts a layer as "not written yet".  The fills run on the
+    // stream of the weight-gradient products (after the products that last read the buffer), so
+    // they stay off the recurrence's path; the first two are needed before anything else.
+    const size_t da_bytes = (size_t)M * 8 * H * e;
+    if (sentinel) {
+        for (int i = 0; i < 2 && i < ctx->L; ++i) {
+            const int db0 = (ctx->L - 1 - i) & 1;
+            RUN_ON(ws, PC_MISC, "sentinel fill of da", launch_fill_bytes16(ctx->ws + ctx->wDA[db0], da_bytes, 0xFFFFFFFFu, ws));
+            if (ov) { HIPCHK("fork", hipEventRecord(ctx->ev_wg[db0], ws)); wg_pending[db0] = true; }
+        }
+    }
     const char* dY;
     int next_buf = 0;
     if (P > 0) {
@@ -488,10 +513,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             const int ncnt = 2 * ctx->rec_nbg * ctx->rec_tiles;
             unsigned short* uht0 = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wUHT) + (size_t)l * 2 * 4 * H * H;
             unsigned short* uht1 = uht0 + (size_t)4 * H * H;
-            RUN(PC_MISC, "U_h transpose", launch_transpose_uh(reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[0][l], e)),
-                                                              reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[1][l], e)),
-                                                              uht0, uht1, H, st));
-            RUN(PC_MISC, "counters", launch_fill_u32(cnt, ncnt, 0u, st));
+            if (!sentinel) RUN(PC_MISC, "counters", launch_fill_u32(cnt, ncnt, 0u, st));
             RecBwdArgs a{};
             a.uht[0] = uht0; a.uht[1] = uht1;
             a.dy = reinterpret_cast<const unsigned short*>(dY);
@@ -499,7 +521,6 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             a.da = reinterpret_cast<unsigned short*>(DA); a.dc = DC;
             a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
-            if (ctx->rec_sync == 1) RUN(PC_MISC, "sentinel fill of da", launch_fill_bytes16(DA, (size_t)M * 8 * H * e, 0xFFFFFFFFu, st));
             RUN(PC_REC_BWD, "persistent recurrent backward", launch_rec_bwd(a, ctx->rec_sync == 1, st, &rec_done));
         }
         for (int n = T - 1; n >= 0 && !rec_done; --n) {
@@ -552,10 +573,6 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             d.C = grad + ctx->off_uh[0][l]; d.ldc = H; d.sC = (long long)(ctx->off_uh[1][l] - ctx->off_uh[0][l]);
             RUN_ON(ws, PC_GEMM_WGRAD, "dU_h", launch_gemm(d, ws));
         }
-        if (ov) {
-            HIPCHK("fork", hipEventRecord(ctx->ev_wg[db], ws));
-            wg_pending[db] = true;
-        }
         if (l > 0) {   // dx = da_fwd W_x_fwd + da_bwd W_x_bwd, the gradient of the layer below's output
             GemmDesc d = gemm_desc(ctx, S, S);
             d.M = M; d.N = Din; d.btrans = true; d.nseg = 2;
@@ -565,6 +582,17 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             RUN(PC_GEMM_DGRAD, "dx", launch_gemm(d, st));
             dY = ctx->ws + ctx->wDY[next_buf];
             next_buf ^= 1;
+        }
+        if (sentinel && l >= 2) {                        // layer l-2 writes this buffer next: refill it once
+            if (ov) {                                    // both its readers (products above, dx) are done
+                HIPCHK("fork", hipEventRecord(ctx->ev_da[db], st));
+                HIPCHK("fork", hipStreamWaitEvent(ws, ctx->ev_da[db], 0));
+            }
+            RUN_ON(ws, PC_MISC, "sentinel fill of da", launch_fill_bytes16(DA, da_bytes, 0xFFFFFFFFu, ws));
+        }
+        if (ov) {
+            HIPCHK("fork", hipEventRecord(ctx->ev_wg[db], ws));
+            wg_pending[db] = true;
         }
     }
     if (ov) {                                            // join: everything on the second stream precedes what follows on st

@@ -64,8 +64,13 @@ int rec_waves_for(int H);
 // *launched is false (and nothing was enqueued) when the grid cannot be co-resident on this device.
 hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bool* launched);
 hipError_t launch_rec_bwd(const RecBwdArgs& a, bool sentinel, hipStream_t st, bool* launched);
-hipError_t launch_transpose_uh(const unsigned short* src0, const unsigned short* src1, unsigned short* dst0,
-                               unsigned short* dst1, int H, hipStream_t st);
+// Transposes `count` matrices U_h [4H][H] (one per layer and direction) into dst + k * 4H*H.
+struct TransposeUhArgs {
+    const unsigned short* src[128];
+    unsigned short* dst;
+    int count;
+};
+hipError_t launch_transpose_uh(const TransposeUhArgs& a, int H, hipStream_t st);
 hipError_t launch_fill_u32(unsigned* p, int n, unsigned v, hipStream_t st);
 // Fills bytes/16 16-byte words with the 32-bit pattern v.
 hipError_t launch_fill_bytes16(void* p, size_t bytes, unsigned v, hipStream_t st);

@@ -501,11 +501,11 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     }
 }
 
-// U_h [4H][H] -> U_h^T [H][4H], 32x32 tiles through LDS; blockIdx.z = direction.
-__global__ __launch_bounds__(256) void transpose_uh_kernel(const bf16_t* src0, const bf16_t* src1, bf16_t* dst0, bf16_t* dst1, int H) {
+// U_h [4H][H] -> U_h^T [H][4H], 32x32 tiles through LDS; blockIdx.z = 2 * layer + direction.
+__global__ __launch_bounds__(256) void transpose_uh_kernel(TransposeUhArgs a, int H) {
     __shared__ bf16_t tile[32][33];
-    const bf16_t* src = blockIdx.z ? src1 : src0;
-    bf16_t* dst = blockIdx.z ? dst1 : dst0;
+    const bf16_t* src = a.src[blockIdx.z];
+    bf16_t* dst = a.dst + (size_t)blockIdx.z * 4 * H * H;
     const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;     // rows of U_h (4H), columns (H)
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     for (int rr = ty; rr < 32; rr += 8) tile[rr][tx] = src[(size_t)(r0 + rr) * H + c0 + tx];
@@ -587,9 +587,9 @@ hipError_t launch_fill_bytes16(void* p, size_t bytes, unsigned v, hipStream_t st
     return hipGetLastError();
 }
 
-hipError_t launch_transpose_uh(const unsigned short* src0, const unsigned short* src1, unsigned short* dst0,
-                               unsigned short* dst1, int H, hipStream_t st) {
-    hipLaunchKernelGGL(transpose_uh_kernel, dim3(H / 32, 4 * H / 32, 2), dim3(256), 0, st, src0, src1, dst0, dst1, H);
+hipError_t launch_transpose_uh(const TransposeUhArgs& a, int H, hipStream_t st) {
+    if (a.count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(transpose_uh_kernel, dim3(H / 32, 4 * H / 32, a.count), dim3(256), 0, st, a, H);
     return hipGetLastError();
 }
 
