@@ -134,6 +134,11 @@ __device__ __forceinline__ bool ensure_written(uint4 (&frag)[NQ], const bf16_t* 
     }
 }
 
+// Barrier for LDS hazards only: waits for this wave's LDS operations, not for its global loads and
+// write-through stores (a full __syncthreads would drain the loads issued ahead for the next item
+// and the acknowledgements of the exchange stores on every item).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 struct GroupMap { int d, u, bg, group; };
 
 // Workgroups that exchange data sit on one XCD when ids are dealt round-robin over eight XCDs
@@ -226,6 +231,10 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     const int nitems = T * ntl;
     float ax[EPT][4], cp[EPT];
     issue_inputs(0, ax, cp);
+    // With several batch tiles per workgroup the next item's h was written a whole frame ago: its
+    // chunks are loaded while this item computes (checked for the sentinel like any other load).
+    uint4 apre[KSTEPS];
+    bool have_pre = false;
     for (int item = 0; item < nitems; ++item) {
         const int n = item / ntl, i = item - n * ntl;
         const int t = d ? T - 1 - n : n;
@@ -247,9 +256,17 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                 // one probe per producing workgroup of this wavefront's k-range: its last unit, last valid row
                 const int prow = min(b0 + 31, B - 1);
                 const bf16_t* probe = a.y + ((size_t)tp * B + prow) * 2 * H + (size_t)d * H + wave * KW + (lane & 3) * 32 + 31;
-                const bool gu = wait_probe(probe, lane < KW / 32, a.abort_word, a.limit_ticks);
-                asm volatile("" ::: "memory");
-                load_chunks_cached<KSTEPS>(afrag, hp, valid);
+                bool got = false, gu = false;
+                if (have_pre) {
+#pragma unroll
+                    for (int q = 0; q < KSTEPS; ++q) afrag[q] = apre[q];
+                    got = all_written<KSTEPS>(afrag);
+                }
+                if (!got) {
+                    gu = wait_probe(probe, lane < KW / 32, a.abort_word, a.limit_ticks);
+                    asm volatile("" ::: "memory");
+                    load_chunks_cached<KSTEPS>(afrag, hp, valid);
+                }
                 if (item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
                 ensure_written<KSTEPS>(afrag, hp, valid, gu, a.abort_word, a.limit_ticks);
             } else {
@@ -268,6 +285,15 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             for (int q = 0; q < KSTEPS; ++q)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) acc[g] = mfma_bf16(afrag[q], bfrag[g][q], acc[g]);
+            have_pre = false;
+            if (SENTINEL && ntl >= 2 && item + 1 < nitems) {
+                const int n2 = (item + 1) / ntl, i2 = (item + 1) - n2 * ntl;
+                const int tp2 = d ? T - n2 : n2 - 1;
+                const int row2 = (gm.bg * a.tiles_per_group + i2) * 32 + l32;
+                const bool valid2 = row2 < B;
+                load_chunks_cached<KSTEPS>(apre, a.y + ((size_t)tp2 * B + (valid2 ? row2 : 0)) * 2 * H + (size_t)d * H + wave * KW + 8 * lh, valid2);
+                have_pre = true;
+            }
             // partial accumulators -> LDS as [wave][gate][reg/4][lane][reg%4]
 #pragma unroll
             for (int g = 0; g < 4; ++g)
@@ -275,7 +301,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                 for (int rq = 0; rq < 4; ++rq)
                     l4[((wave * 4 + g) * 4 + rq) * 64 + lane] =
                         make_float4(acc[g][4 * rq], acc[g][4 * rq + 1], acc[g][4 * rq + 2], acc[g][4 * rq + 3]);
-            __syncthreads();
+            if (SENTINEL) lds_barrier(); else __syncthreads();
 #pragma unroll
             for (int w2 = 0; w2 < NW; ++w2)
 #pragma unroll
@@ -314,7 +340,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                 if (SENTINEL) st_coh_bf16(yp, h); else *yp = f2bf(h);
             }
         }
-        if (SENTINEL) __syncthreads();                   // frees the LDS buffer for the next item
+        if (SENTINEL) lds_barrier();                     // frees the LDS buffer for the next item
         else signal_counter(cnt + i);                    // barrier inside: same role
         // saved for the backward pass only: off the critical path of the exchange
 #pragma unroll
@@ -396,6 +422,8 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     const int nitems = T * ntl;
     Inputs cur;
     if (AHEAD) issue_inputs(0, cur);
+    uint4 apre[8];                                       // first slab of the next item, loaded ahead (several tiles only)
+    bool have_pre = false;
     for (int item = 0; item < nitems; ++item) {
         if (!AHEAD) issue_inputs(item, cur);
         const int ni = item / ntl, i = item - ni * ntl;
@@ -419,14 +447,36 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 // then stream the slabs of 128 gate rows with the next slab's loads in flight
                 const int prow = min(b0 + 31, B - 1);
                 const bf16_t* probe = a.da + ((size_t)tn * B + prow) * 8 * H + (size_t)d * 4 * H + wave * KWB + (lane & 15) * 32 + 31;
-                bool gu = wait_probe(probe, lane < 16, a.abort_word, a.limit_ticks);
-                asm volatile("" ::: "memory");
                 uint4 afrag[2][8];
-                load_chunks_cached<8>(afrag[0], ap, valid);
+                bool got = false, gu = false;
+                if (have_pre) {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) afrag[0][q] = apre[q];
+                    got = all_written<8>(afrag[0]);
+                }
+                if (!got) {
+                    gu = wait_probe(probe, lane < 16, a.abort_word, a.limit_ticks);
+                    asm volatile("" ::: "memory");
+                    load_chunks_cached<8>(afrag[0], ap, valid);
+                }
 #pragma unroll
                 for (int sl = 0; sl < KSTEPS / 8; ++sl) {
                     if (sl + 1 < KSTEPS / 8) load_chunks_cached<8>(afrag[(sl + 1) & 1], ap + (sl + 1) * 128, valid);
-                    else if (AHEAD && item + 1 < nitems) issue_inputs(item + 1, nxt);
+                    else {
+                        if (AHEAD && item + 1 < nitems) issue_inputs(item + 1, nxt);
+                        have_pre = false;
+                        if (ntl >= 2 && item + 1 < nitems) {
+                            const int ni2 = (item + 1) / ntl, i2 = (item + 1) - ni2 * ntl;
+                            const int n2 = T - 1 - ni2;
+                            if (n2 < T - 1) {
+                                const int tn2 = d ? T - 2 - n2 : n2 + 1;
+                                const int row2 = (gm.bg * a.tiles_per_group + i2) * 32 + l32;
+                                const bool valid2 = row2 < B;
+                                load_chunks_cached<8>(apre, a.da + ((size_t)tn2 * B + (valid2 ? row2 : 0)) * 8 * H + (size_t)d * 4 * H + wave * KWB + 8 * lh, valid2);
+                                have_pre = true;
+                            }
+                        }
+                    }
                     gu = ensure_written<8>(afrag[sl & 1], ap + sl * 128, valid, gu, a.abort_word, a.limit_ticks);
 #pragma unroll
                     for (int q = 0; q < 8; ++q) acc = mfma_bf16(afrag[sl & 1][q], bfrag[sl * 8 + q], acc);
@@ -447,7 +497,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq)
                 l4[(wave * 4 + rq) * 64 + lane] = make_float4(acc[4 * rq], acc[4 * rq + 1], acc[4 * rq + 2], acc[4 * rq + 3]);
-            __syncthreads();
+            if (SENTINEL) lds_barrier(); else __syncthreads();
 #pragma unroll
             for (int w2 = 0; w2 < NW; ++w2)
 #pragma unroll
@@ -482,7 +532,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 }
             }
         }
-        if (SENTINEL) __syncthreads();
+        if (SENTINEL) lds_barrier();
         else signal_counter(cnt + i);
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
