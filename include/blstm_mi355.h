@@ -112,7 +112,7 @@ int adpsgd_mix(float* const* theta_master, void* const* theta_bf16_or_null, size
 int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
 
 /* Options.  BLSTM_OPT_RECURRENT_PATH: 0 (default) runs each layer's T recurrent frames in one
-   persistent kernel where the shape allows it (mode 1, H a multiple of 128 up to 512, grid
+   persistent kernel where the shape allows it (mode 1, H one of 128, 256, 512, 1024, grid
    co-resident on the device), 1 forces one launch per frame everywhere. */
 #define BLSTM_OPT_RECURRENT_PATH 1
 /* BLSTM_OPT_RECURRENT_SYNC (default 1): how the workgroups of a persistent kernel exchange h / dE/da

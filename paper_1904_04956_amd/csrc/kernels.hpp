@@ -35,7 +35,7 @@ struct CellBwdArgs {
 };
 hipError_t launch_cell_bwd(const CellBwdArgs& a, DType store, hipStream_t s);
 
-// ---- persistent recurrent kernels (bf16 storage, H a multiple of 128 up to 512) -------------------
+// ---- persistent recurrent kernels (bf16 storage, H one of 128, 256, 512, 1024) -------------------
 struct RecFwdArgs {
     const unsigned short* uh[2];  // U_h per direction, [4H][H]
     const float* ax;              // W_x x + b for every frame, [M][8H]

@@ -26,7 +26,6 @@
 namespace blstm {
 namespace {
 
-constexpr int KW = 128;                                  // contraction elements per wavefront (forward)
 constexpr unsigned SENT16 = 0xFFFFu;
 
 __device__ __forceinline__ f32x16_t mfma_bf16(const uint4& a, const uint4& b, f32x16_t c) {
@@ -179,7 +178,8 @@ __device__ __forceinline__ int tiles_in_batch(int bg, int tiles_per_group, int B
 }
 
 // ------------------------------------------------------------------------------ forward
-template <int NW, bool SENTINEL>
+// KW = contraction elements per wavefront: H = NW * KW.
+template <int NW, int KW, bool SENTINEL>
 __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     constexpr int EPT = 16 / NW;                         // accumulator registers (batch rows) per thread
     constexpr int KSTEPS = KW / 16;                      // MFMA steps per gate per wavefront
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             if (SENTINEL) {
                 // one probe per producing workgroup of this wavefront's k-range: its last unit, last valid row
                 const int prow = min(b0 + 31, B - 1);
-                const bf16_t* probe = a.y + ((size_t)tp * B + prow) * 2 * H + (size_t)d * H + wave * KW + (lane & 3) * 32 + 31;
+                const bf16_t* probe = a.y + ((size_t)tp * B + prow) * 2 * H + (size_t)d * H + wave * KW + (lane & (KW / 32 - 1)) * 32 + 31;
                 bool got = false, gu = false;
                 if (have_pre) {
 #pragma unroll
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) acc[g] = mfma_bf16(afrag[q], bfrag[g][q], acc[g]);
             have_pre = false;
-            if (SENTINEL && ntl >= 2 && item + 1 < nitems) {
+            if (SENTINEL && KW == 128 && ntl >= 2 && item + 1 < nitems) {
                 const int n2 = (item + 1) / ntl, i2 = (item + 1) - n2 * ntl;
                 const int tp2 = d ? T - n2 : n2 - 1;
                 const int row2 = (gm.bg * a.tiles_per_group + i2) * 32 + l32;
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------ backward
-template <int NW, bool SENTINEL>
+template <int NW, int KW, bool SENTINEL>
 __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     constexpr int EPT = 16 / NW;
     constexpr int KSTEPS = 4 * KW / 16;                  // the contraction runs over the 4H gate rows
@@ -446,7 +446,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 // the gate rows of this wavefront come from KWB/32 producers: probe each one's last unit,
                 // then stream the slabs of 128 gate rows with the next slab's loads in flight
                 const int prow = min(b0 + 31, B - 1);
-                const bf16_t* probe = a.da + ((size_t)tn * B + prow) * 8 * H + (size_t)d * 4 * H + wave * KWB + (lane & 15) * 32 + 31;
+                const bf16_t* probe = a.da + ((size_t)tn * B + prow) * 8 * H + (size_t)d * 4 * H + wave * KWB + (lane & (4 * KW / 32 - 1)) * 32 + 31;
                 uint4 afrag[2][8];
                 bool got = false, gu = false;
                 if (have_pre) {
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                     got = all_written<8>(afrag[0]);
                 }
                 if (!got) {
-                    gu = wait_probe(probe, lane < 16, a.abort_word, a.limit_ticks);
+                    gu = wait_probe(probe, lane < 4 * KW / 32, a.abort_word, a.limit_ticks);
                     asm volatile("" ::: "memory");
                     load_chunks_cached<8>(afrag[0], ap, valid);
                 }
@@ -465,7 +465,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                     else {
                         if (AHEAD && item + 1 < nitems) issue_inputs(item + 1, nxt);
                         have_pre = false;
-                        if (ntl >= 2 && item + 1 < nitems) {
+                        if (KW == 128 && ntl >= 2 && item + 1 < nitems) {
                             const int ni2 = (item + 1) / ntl, i2 = (item + 1) - ni2 * ntl;
                             const int n2 = T - 1 - ni2;
                             if (n2 < T - 1) {
@@ -593,33 +593,36 @@ hipError_t prepare(K kernel, int threads, size_t dyn_lds, int grid, bool* fits) 
     return hipSuccess;
 }
 
-template <int NW, bool S>
+template <int NW, int KW, bool S>
 hipError_t run_fwd(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
     const size_t lds = (size_t)NW * 4 * 4 * 64 * 16;
     bool fits = false;
-    hipError_t e = prepare(rec_fwd_kernel<NW, S>, 64 * NW, lds, grid, &fits);
+    hipError_t e = prepare(rec_fwd_kernel<NW, KW, S>, 64 * NW, lds, grid, &fits);
     if (e != hipSuccess || !fits) return e;
-    hipLaunchKernelGGL((rec_fwd_kernel<NW, S>), dim3(grid), dim3(64 * NW), lds, st, a);
+    hipLaunchKernelGGL((rec_fwd_kernel<NW, KW, S>), dim3(grid), dim3(64 * NW), lds, st, a);
     *launched = true;
     return hipGetLastError();
 }
-template <int NW, bool S>
+template <int NW, int KW, bool S>
 hipError_t run_bwd(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
     const size_t lds = (size_t)NW * 4 * 64 * 16;
     bool fits = false;
-    hipError_t e = prepare(rec_bwd_kernel<NW, S>, 64 * NW, lds, grid, &fits);
+    hipError_t e = prepare(rec_bwd_kernel<NW, KW, S>, 64 * NW, lds, grid, &fits);
     if (e != hipSuccess || !fits) return e;
-    hipLaunchKernelGGL((rec_bwd_kernel<NW, S>), dim3(grid), dim3(64 * NW), lds, st, a);
+    hipLaunchKernelGGL((rec_bwd_kernel<NW, KW, S>), dim3(grid), dim3(64 * NW), lds, st, a);
     *launched = true;
     return hipGetLastError();
 }
 
 }  // namespace
 
+// Supported widths: H = 128, 256, 512 (one, two, four wavefronts with 128 contraction elements each)
+// and H = 1024 (four wavefronts with 256 each: the U_h slice then fills 256 registers per lane).
 int rec_waves_for(int H) {
-    if (H % KW != 0) return 0;
-    const int nw = H / KW;
-    return (nw == 1 || nw == 2 || nw == 4) ? nw : 0;
+    if (H == 128) return 1;
+    if (H == 256) return 2;
+    if (H == 512 || H == 1024) return 4;
+    return 0;
 }
 
 hipError_t launch_fill_u32(unsigned* p, int n, unsigned v, hipStream_t st) {
@@ -646,10 +649,11 @@ hipError_t launch_transpose_uh(const TransposeUhArgs& a, int H, hipStream_t st) 
 hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bool* launched) {
     *launched = false;
     const int grid = 2 * a.nbg * (a.H / 32);
-    switch (rec_waves_for(a.H)) {
-        case 1: return sentinel ? run_fwd<1, true>(a, grid, st, launched) : run_fwd<1, false>(a, grid, st, launched);
-        case 2: return sentinel ? run_fwd<2, true>(a, grid, st, launched) : run_fwd<2, false>(a, grid, st, launched);
-        case 4: return sentinel ? run_fwd<4, true>(a, grid, st, launched) : run_fwd<4, false>(a, grid, st, launched);
+    switch (a.H) {
+        case 128: return sentinel ? run_fwd<1, 128, true>(a, grid, st, launched) : run_fwd<1, 128, false>(a, grid, st, launched);
+        case 256: return sentinel ? run_fwd<2, 128, true>(a, grid, st, launched) : run_fwd<2, 128, false>(a, grid, st, launched);
+        case 512: return sentinel ? run_fwd<4, 128, true>(a, grid, st, launched) : run_fwd<4, 128, false>(a, grid, st, launched);
+        case 1024: return sentinel ? run_fwd<4, 256, true>(a, grid, st, launched) : run_fwd<4, 256, false>(a, grid, st, launched);
         default: return hipSuccess;
     }
 }
@@ -657,10 +661,11 @@ hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bo
 hipError_t launch_rec_bwd(const RecBwdArgs& a, bool sentinel, hipStream_t st, bool* launched) {
     *launched = false;
     const int grid = 2 * a.nbg * (a.H / 32);
-    switch (rec_waves_for(a.H)) {
-        case 1: return sentinel ? run_bwd<1, true>(a, grid, st, launched) : run_bwd<1, false>(a, grid, st, launched);
-        case 2: return sentinel ? run_bwd<2, true>(a, grid, st, launched) : run_bwd<2, false>(a, grid, st, launched);
-        case 4: return sentinel ? run_bwd<4, true>(a, grid, st, launched) : run_bwd<4, false>(a, grid, st, launched);
+    switch (a.H) {
+        case 128: return sentinel ? run_bwd<1, 128, true>(a, grid, st, launched) : run_bwd<1, 128, false>(a, grid, st, launched);
+        case 256: return sentinel ? run_bwd<2, 128, true>(a, grid, st, launched) : run_bwd<2, 128, false>(a, grid, st, launched);
+        case 512: return sentinel ? run_bwd<4, 128, true>(a, grid, st, launched) : run_bwd<4, 128, false>(a, grid, st, launched);
+        case 1024: return sentinel ? run_bwd<4, 256, true>(a, grid, st, launched) : run_bwd<4, 256, false>(a, grid, st, launched);
         default: return hipSuccess;
     }
 }
