@@ -25,6 +25,16 @@ PEAK_BF16_MFMA = 2.5e15      # FLOP/s, dense
 PEAK_FP32_MFMA = 157.3e12
 PEAK_HBM = 8.0e12            # B/s
 
+# HBM bytes per launch (fetch + write) of kernel classes, from rocprofv3 --pmc runs of this script
+# (FETCH_SIZE and WRITE_SIZE, each scaled by its reading for the 1 GiB copy of --traffic-calibration);
+# the runs and figures are in profiles/hbm_traffic_paper4x512.txt.  Keyed by (workload, batch, class).
+MEASURED_HBM_BYTES_PER_LAUNCH = {
+    ("paper4x512", 256, "recurrent_bwd_persistent"): (2 * 75265.5 + 44214.6) * 1024,
+    ("paper4x512", 256, "recurrent_fwd_persistent"): (2 * 74938.1 + 75264.0) * 1024,
+    ("paper4x512", 256, "gemm_logits"): (2 * 51845.2 + 336000.0) * 1024,
+}
+MEASURED_MIX_BYTES_PER_PAIR = {"paper4x512": (2 * 119318.1 + 357950.8) * 1024}   # one launch on two replicas
+
 
 def flops_by_class(T, B, D, H, L, P, V):
     """Algorithmic FLOP of one step per kernel class (2 FLOP per multiply-add), and launches."""
@@ -38,6 +48,9 @@ def flops_by_class(T, B, D, H, L, P, V):
     f["gemm_logits"] = (2 * M * V * Z, 1)
     f["gemm_softmax_bwd"] = (2 * 2 * M * V * Z, 2)
     f["gemm_recurrent_bwd"] = (L * (T - 1) * 2 * (2 * B * 4 * H * H), L * (T - 1))
+    # the persistent kernels do a whole layer (both directions, all frames) per launch
+    f["recurrent_fwd_persistent"] = (f["gemm_recurrent_fwd"][0], L)
+    f["recurrent_bwd_persistent"] = (f["gemm_recurrent_bwd"][0], L)
     f["gemm_wgrad"] = (sum(2 * M * 8 * H * d for d in din) + L * 2 * (T - 1) * B * 8 * H * H + 2 * M * P * 2 * H,
                        2 * L + (1 if P > 0 else 0))
     f["gemm_dgrad"] = (sum(2 * M * 8 * H * d for d in din[1:]) + 2 * M * 2 * H * P, L - 1 + (1 if P > 0 else 0))
@@ -65,6 +78,8 @@ def main():
     ap.add_argument("--rec-path", type=int, default=0, help="1 = one launch per frame")
     ap.add_argument("--overlap", type=int, default=-1, help="0 = weight-gradient products on the caller's stream")
     ap.add_argument("--mix-replicas", type=int, default=16, help="replicas of the separate adpsgd_mix measurement")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="first copy 1 GiB three times with a plain copy kernel (reference for HBM counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (one learner per GPU, no collectives); use --gpus 1")
@@ -83,6 +98,14 @@ def main():
         d["B"] = args.batch
     T, B = d["T"], d["B"]
     bf = w.mode == 1
+
+    if args.traffic_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     lrn = Learner(mode=w.mode, recurrent_path=args.rec_path, **d)
     if args.rec_sync >= 0:
@@ -133,7 +156,10 @@ def main():
     }
 
     # ---- per-kernel-class durations: HIP events recorded by the library on the launch stream ----
+    # (everything on one stream for this pass: events around a launch that shares the device with the
+    #  second stream's products would time the sharing, not the kernel)
     if not args.no_profile:
+        bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_OVERLAP, 0)
         bl.blstm_profile_enable(lrn.ctx, 1)
         nprof = min(args.steps, 10)
         for _ in range(nprof):
@@ -141,6 +167,7 @@ def main():
         torch.cuda.synchronize()
         prof = bl.blstm_profile_read(lrn.ctx)
         bl.blstm_profile_enable(lrn.ctx, 0)
+        bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_OVERLAP, args.overlap if args.overlap >= 0 else 2)
         fl = flops_by_class(T, B, d["D"], d["H"], d["L"], d["P"], d["V"])
         classes = {}
         for name, (ms, cnt) in prof.items():
@@ -151,15 +178,22 @@ def main():
                 ent["tflops"] = fl[name][0] / (ms / nprof * 1e-3) / 1e12
             classes[name] = ent
         out["kernel_classes"] = classes
-        gemm = {k: v for k, v in classes.items() if k in fl and fl[k][0] > 0}
-        if gemm:
-            dom = max(gemm, key=lambda k: gemm[k]["ms_per_step"])
-            launches = gemm[dom]["launches_per_step"]
-            flop_launch = fl[dom][0] / launches
-            achieved = flop_launch / (gemm[dom]["avg_launch_us"] * 1e-6) / 1e12
-            out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak / 1e12,
-                               "unit": "TFLOP/s", "frac": achieved * 1e12 / peak, "traffic": None,
-                               "flop_per_launch": flop_launch, "avg_launch_us": gemm[dom]["avg_launch_us"]}
+        def roofline_of(name):
+            launches = classes[name]["launches_per_step"]
+            flop_launch = fl[name][0] / launches
+            achieved = flop_launch / (classes[name]["avg_launch_us"] * 1e-6) / 1e12
+            key = (w.name, B, name)
+            return {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": peak / 1e12, "unit": "TFLOP/s",
+                    "frac": achieved * 1e12 / peak, "traffic": MEASURED_HBM_BYTES_PER_LAUNCH.get(key),
+                    "flop_per_launch": flop_launch, "avg_launch_us": classes[name]["avg_launch_us"]}
+
+        with_flop = {k: v for k, v in classes.items() if k in fl and fl[k][0] > 0}
+        if with_flop:
+            # the class that takes the most time, and the plain product class that takes the most time
+            out["roofline"] = roofline_of(max(with_flop, key=lambda k: with_flop[k]["ms_per_step"]))
+            gemm = {k: v for k, v in with_flop.items() if k.startswith("gemm_")}
+            if gemm:
+                out["roofline_gemm"] = roofline_of(max(gemm, key=lambda k: gemm[k]["ms_per_step"]))
 
     # ---- the averaging kernel on R replicas of this model, against HBM bandwidth ----------------
     R = args.mix_replicas
@@ -182,7 +216,9 @@ def main():
         gbs = bytes_per / (mix_ms * 1e-3) / 1e9
         out["adpsgd_mix"] = {"replicas": R, "params": lrn.n, "ms": mix_ms, "bound": "hbm", "achieved": gbs,
                              "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": gbs * 1e9 / PEAK_HBM,
-                             "bytes_per_launch": bytes_per}
+                             "bytes_per_launch": bytes_per,
+                             "traffic": (MEASURED_MIX_BYTES_PER_PAIR[w.name] * R / 2
+                                         if w.name in MEASURED_MIX_BYTES_PER_PAIR and B == w.dims()["B"] else None)}
         del reps, shs
 
     # ---- the oracle on this machine's host cores, on a bounded sample of the same workload ------
@@ -192,18 +228,23 @@ def main():
         dd = dict(d); dd["B"] = Bs
         dm = orc.Dims(**dd)
         th64 = theta.astype(np.float64)
+        nb64 = th64.copy()
+        nsteps, cdt = 0, 0.0
         t0 = time.perf_counter()
-        _, g = orc.loss_and_grad(dm, th64, x[:, :Bs], labels[:, :Bs])
-        orc.sgd_step(th64, g, w.lr)
-        cdt = time.perf_counter() - t0
+        while nsteps < 2 or (cdt < 12.0 and nsteps < 50):     # about 12 s of oracle steps on the sample
+            _, g = orc.loss_and_grad(dm, th64, x[:, :Bs], labels[:, :Bs])
+            th64, _ = orc.sgd_step(th64, g, w.lr)
+            th64, nb64 = orc.adpsgd_mix([th64, nb64], [1, 0])
+            nsteps += 1
+            cdt = time.perf_counter() - t0
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count()
-        out["cpu_baseline"] = {"value": T * Bs / cdt, "unit": "frames/s", "cores": cores, "kind": "oracle",
-                               "sample": f"one step (loss, gradient, SGD) of the same model on the first {Bs} of {B} "
-                                         f"sequences, float64 numpy, {cdt:.1f} s"}
+        out["cpu_baseline"] = {"value": T * Bs * nsteps / cdt, "unit": "frames/s", "cores": cores, "kind": "oracle",
+                               "sample": f"{nsteps} steps (loss, gradient, SGD update, pair averaging) of the same model on the "
+                                         f"first {Bs} of {B} sequences, float64 numpy, {cdt:.1f} s"}
     lrn.close()
     print(json.dumps(out))
 

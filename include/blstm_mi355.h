@@ -121,9 +121,11 @@ int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
    stored write-through and loaded cache-bypassing at agent scope, and a consumer proceeds once
    none of the elements it needs still holds the pattern (each element is its own ready flag). */
 #define BLSTM_OPT_RECURRENT_SYNC 2
-/* BLSTM_OPT_OVERLAP (default 1): blstm_backward runs the weight-gradient products on a second stream
-   owned by the context (default priority), forked from and joined to the caller's stream with events,
-   so that they overlap the next layer's recurrence.  0 keeps everything on the caller's stream. */
+/* BLSTM_OPT_OVERLAP: 1 = blstm_backward runs the weight-gradient products on a second stream owned by
+   the context (default priority), forked from and joined to the caller's stream with events, so that
+   they overlap the next layer's recurrence; 0 keeps everything on the caller's stream; 2 (default)
+   chooses by shape: the second stream is used when each workgroup of the persistent recurrent kernel
+   owns a single batch tile (the recurrence is then latency-bound and leaves the device underused). */
 #define BLSTM_OPT_OVERLAP 3
 int blstm_set_option(blstm_ctx* ctx, int option, int value);
 

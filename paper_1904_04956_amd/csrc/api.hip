@@ -63,7 +63,7 @@ struct blstm_ctx {
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
-    int overlap;              // 1: weight-gradient products run on a second stream beside the next layer's recurrence
+    int overlap;              // weight-gradient products on a second stream beside the next layer's recurrence: 0 never, 1 always, 2 by shape
     hipStream_t side;         // created on first use
     hipEvent_t ev_fork, ev_da[2], ev_wg[2], ev_join;
     bool side_ready;
@@ -234,7 +234,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
         c->wPART2 = w; c->part2_bytes = up256(need2);
         w += c->part2_bytes;
     }
-    c->overlap = 1; c->side = nullptr; c->side_ready = false;
+    c->overlap = 2; c->side = nullptr; c->side_ready = false;
     c->ws_bytes = w;
     c->ws = nullptr; c->ws_bound = 0; c->have_forward = false;
     c->prof = false; c->recs_used = 0;
@@ -435,7 +435,9 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
     // the next layer's (latency-bound) recurrence: fork after each layer's dE/da is complete, join at
     // the end.  dE/da alternates between two buffers so that a layer's products can still read theirs
     // while the next layer writes the other.
-    const bool ov = ctx->overlap != 0;
+    // By shape: the second stream pays while the recurrence is latency-bound (one batch tile per
+    // workgroup); with several tiles per workgroup it is throughput-bound and the two only compete.
+    const bool ov = ctx->overlap == 1 || (ctx->overlap == 2 && ctx->rec_nbg > 0 && ctx->rec_path == 0 && ctx->rec_tiles <= 1);
     hipStream_t ws = st;                                 // stream of the weight-gradient products
     if (ov) {
         HIPCHK("second stream", ensure_side(ctx));
@@ -656,7 +658,7 @@ int blstm_set_option(blstm_ctx* c, int option, int value) {
     if (!c) return fail(BLSTM_ERR_NULL, "blstm_set_option: null argument");
     if (option == BLSTM_OPT_RECURRENT_PATH && (value == 0 || value == 1)) { c->rec_path = value; return BLSTM_OK; }
     if (option == BLSTM_OPT_RECURRENT_SYNC && (value == 0 || value == 1)) { c->rec_sync = value; return BLSTM_OK; }
-    if (option == BLSTM_OPT_OVERLAP && (value == 0 || value == 1)) { c->overlap = value; return BLSTM_OK; }
+    if (option == BLSTM_OPT_OVERLAP && value >= 0 && value <= 2) { c->overlap = value; return BLSTM_OK; }
     return fail(BLSTM_ERR_DIM, "blstm_set_option: unknown option %d or value %d", option, value);
 }
 

@@ -139,19 +139,19 @@ __device__ __forceinline__ void gload_rowfast(uint4 (&r)[NCH], const Operand& op
 // ---- unguarded forms: tile fully inside the matrices, K a multiple of the slab, aligned -------
 // `base` is uniform (tile origin and slab applied, in bytes); `voff` is this thread's byte offset.
 template <typename T, int NCH>
-__device__ __forceinline__ void gload_kfast_fast(uint4 (&r)[NCH], const char* base, long long rowstep, uint32_t voff) {
+__device__ __forceinline__ void gload_kfast_fast(uint4 (&r)[NCH], const char* base, long long rowstep, uint32_t voff) {  // rowstep: bytes per pass of rows
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         const u32x4_t v = *reinterpret_cast<const u32x4_t*>(base + i * rowstep + voff);
         r[i] = make_uint4(v[0], v[1], v[2], v[3]);
     }
 }
-template <typename T, int NCH>
+template <typename T, int NCH, int PR>
 __device__ __forceinline__ void gload_rowfast_fast(uint4 (&r)[NCH], const char* base, long long kstep, uint32_t voff) {
     constexpr int VEC = Vec<T>::N;
 #pragma unroll
     for (int pass = 0; pass < NCH / 4; ++pass) {
-        const char* pb = base + pass * 128 * (int)sizeof(T) + voff;
+        const char* pb = base + pass * PR * (int)sizeof(T) + voff;
         if (sizeof(T) == 4) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -170,12 +170,12 @@ __device__ __forceinline__ void gload_rowfast_fast(uint4 (&r)[NCH], const char* 
 
 // LDS stores through offsets computed once per thread (uint4 units): soff for the K-fast form,
 // soffj[j] for row j of the four-row group of the row-fast form.
-template <int NCH>
+template <int NCH, int RP>
 __device__ __forceinline__ void sstore_kfast_off(uint4* s, const uint4 (&r)[NCH], int soff) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) s[soff + i * 32 * CHUNKS] = r[i];
+    for (int i = 0; i < NCH; ++i) s[soff + i * RP * CHUNKS] = r[i];
 }
-template <typename T, int NCH>
+template <typename T, int NCH, int PR>
 __device__ __forceinline__ void sstore_rowfast_off(uint4* s, const uint4 (&r)[NCH], const int (&soffj)[4]) {
 #pragma unroll
     for (int pass = 0; pass < NCH / 4; ++pass) {
@@ -184,7 +184,7 @@ __device__ __forceinline__ void sstore_rowfast_off(uint4* s, const uint4 (&r)[NC
             const uint32_t a[4][4] = {{rp[0].x, rp[0].y, rp[0].z, rp[0].w}, {rp[1].x, rp[1].y, rp[1].z, rp[1].w},
                                       {rp[2].x, rp[2].y, rp[2].z, rp[2].w}, {rp[3].x, rp[3].y, rp[3].z, rp[3].w}};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) s[soffj[j] + pass * 128 * CHUNKS] = make_uint4(a[0][j], a[1][j], a[2][j], a[3][j]);
+            for (int j = 0; j < 4; ++j) s[soffj[j] + pass * PR * CHUNKS] = make_uint4(a[0][j], a[1][j], a[2][j], a[3][j]);
         } else {
             const uint32_t L[8][2] = {{rp[0].x, rp[0].y}, {rp[0].z, rp[0].w}, {rp[1].x, rp[1].y}, {rp[1].z, rp[1].w},
                                       {rp[2].x, rp[2].y}, {rp[2].z, rp[2].w}, {rp[3].x, rp[3].y}, {rp[3].z, rp[3].w}};
@@ -196,7 +196,7 @@ __device__ __forceinline__ void sstore_rowfast_off(uint4* s, const uint4 (&r)[NC
                     uint32_t lo = L[2 * q][j >> 1], hi = L[2 * q + 1][j >> 1];
                     w[q] = (j & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                 }
-                s[soffj[j] + pass * 128 * CHUNKS] = make_uint4(w[0], w[1], w[2], w[3]);
+                s[soffj[j] + pass * PR * CHUNKS] = make_uint4(w[0], w[1], w[2], w[3]);
             }
         }
     }
@@ -217,18 +217,22 @@ __device__ __forceinline__ void mma(f32x16_t& acc, const uint4& a, const uint4& 
     }
 }
 
-template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, bool FAST, bool RS>
-__global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS>
+__global__ __launch_bounds__(128 * WN, 2) void gemm_kernel(Params P) {
+    static_assert(WN == 2 || (FAST && !RS), "the eight-wave shape exists in the unguarded form only");
+    constexpr int NT = 128 * WN;                        // threads: 2 x WN wavefronts
     constexpr int VEC = Vec<TI>::N;
     constexpr int BK = CHUNKS * VEC;
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int NCA = BM / 32, NCB = BN / 32;         // 16-byte chunks staged per thread and slab
+    constexpr int BM = 64 * TM, BN = 32 * TN * WN;
+    constexpr int RP = NT / 8;                          // rows one pass of K-fast loads covers
+    constexpr int PR = NT / 2;                          // rows one pass of row-fast loads covers
+    constexpr int NCA = BM * 8 / NT, NCB = BN * 8 / NT; // 16-byte chunks staged per thread and slab
     extern __shared__ uint4 smem[];                     // [2][(BM + BN) * CHUNKS]
     constexpr int STAGE = (BM + BN) * CHUNKS;           // 16-byte words per buffer: A rows, then B rows
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
     // Workgroup ids are dealt round-robin to the eight XCDs; give each XCD a contiguous
     // range of tiles so that its L2 sees neighbouring tiles, then walk the range in bands
@@ -293,8 +297,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
     // per-thread LDS offsets (uint4 units), computed once
     const int soff_k = (tid >> 3) * CHUNKS + ((tid & 7) ^ swz(tid >> 3));
     int soff_r[4];
+    const int rsub = (tid >> 8) * 128 + (tid & 31) * 4;   // row-fast form: first of this thread's four rows in a pass
+    const int kch = (tid >> 5) & 7;                        // ... and its K chunk
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { const int r = (tid & 31) * 4 + j; soff_r[j] = r * CHUNKS + ((tid >> 5) ^ swz(r)); }
+    for (int j = 0; j < 4; ++j) { const int r = rsub + j; soff_r[j] = r * CHUNKS + (kch ^ swz(r)); }
     const int arow = wm * (32 * TM) + (lane & 31);
     const int brow = wn * (32 * TN) + (lane & 31);
     int roff_a[CHUNKS / 2], roff_b[CHUNKS / 2];
@@ -305,13 +311,15 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
     }
     // per-thread global byte offsets of the unguarded loads
     constexpr int ES = (int)sizeof(TI);
-    const uint32_t voff_a = AT ? (uint32_t)((tid >> 5) * VEC * a0.ld * ES + (tid & 31) * 4 * ES)
+    const uint32_t voff_a = AT ? (uint32_t)(kch * VEC * a0.ld * ES + rsub * ES)
                                : (uint32_t)((tid >> 3) * a0.ld * ES + (tid & 7) * 16);
-    const uint32_t voff_b = BT ? (uint32_t)((tid >> 5) * VEC * b0.ld * ES + (tid & 31) * 4 * ES)
+    const uint32_t voff_b = BT ? (uint32_t)(kch * VEC * b0.ld * ES + rsub * ES)
                                : (uint32_t)((tid >> 3) * b0.ld * ES + (tid & 7) * 16);
 
-    uint4 ra[NCA], rb[NCB];
-    auto gload = [&](int it) {
+    // Two sets of staging registers: the loads of slab it + 2 are issued while slab it is multiplied
+    // and slab it + 1 (loaded one iteration earlier) waits in the other set for its LDS buffer.
+    uint4 ra0[NCA], rb0[NCB], ra1[NCA], rb1[NCB];
+    auto gload = [&](int it, uint4 (&ra)[NCA], uint4 (&rb)[NCB]) {
         const bool s = it >= ntiles[0];
         const int k0 = (it - (s ? ntiles[0] : 0)) * BK;
         Operand oa, ob;
@@ -321,10 +329,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
             // (both segments of a two-segment product share their leading dimensions in this mode)
             const char* pa = static_cast<const char*>(oa.p);
             const char* pb = static_cast<const char*>(ob.p);
-            if constexpr (AT) gload_rowfast_fast<TI, NCA>(ra, pa + ((long long)k0 * oa.ld + row0) * ES, oa.ld * ES, voff_a);
-            else    gload_kfast_fast<TI, NCA>(ra, pa + ((long long)row0 * oa.ld + k0) * ES, 32 * oa.ld * ES, voff_a);
-            if constexpr (BT) gload_rowfast_fast<TI, NCB>(rb, pb + ((long long)k0 * ob.ld + col0) * ES, ob.ld * ES, voff_b);
-            else    gload_kfast_fast<TI, NCB>(rb, pb + ((long long)col0 * ob.ld + k0) * ES, 32 * ob.ld * ES, voff_b);
+            if constexpr (AT) gload_rowfast_fast<TI, NCA, PR>(ra, pa + ((long long)k0 * oa.ld + row0) * ES, oa.ld * ES, voff_a);
+            else    gload_kfast_fast<TI, NCA>(ra, pa + ((long long)row0 * oa.ld + k0) * ES, RP * oa.ld * ES, voff_a);
+            if constexpr (BT) gload_rowfast_fast<TI, NCB, PR>(rb, pb + ((long long)k0 * ob.ld + col0) * ES, ob.ld * ES, voff_b);
+            else    gload_kfast_fast<TI, NCB>(rb, pb + ((long long)col0 * ob.ld + k0) * ES, RP * ob.ld * ES, voff_b);
         } else {
             const int K = s ? K1 : K0;
             if constexpr (AT) gload_rowfast<TI, NCA>(ra, oa, row0, K, k0, tid);
@@ -333,11 +341,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
             else              gload_kfast<TI, NCB>(rb, ob, col0, K, k0, tid);
         }
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](int buf, const uint4 (&ra)[NCA], const uint4 (&rb)[NCB]) {
         uint4* a_s = smem + buf * STAGE;
         uint4* b_s = a_s + BM * CHUNKS;
-        if constexpr (AT) sstore_rowfast_off<TI, NCA>(a_s, ra, soff_r); else sstore_kfast_off<NCA>(a_s, ra, soff_k);
-        if constexpr (BT) sstore_rowfast_off<TI, NCB>(b_s, rb, soff_r); else sstore_kfast_off<NCB>(b_s, rb, soff_k);
+        if constexpr (AT) sstore_rowfast_off<TI, NCA, PR>(a_s, ra, soff_r); else sstore_kfast_off<NCA, RP>(a_s, ra, soff_k);
+        if constexpr (BT) sstore_rowfast_off<TI, NCB, PR>(b_s, rb, soff_r); else sstore_kfast_off<NCB, RP>(b_s, rb, soff_k);
     };
     auto lfrag = [&](const uint4* a_s, const uint4* b_s, int q, uint4 (&af)[TM], uint4 (&bf)[TN]) {
 #pragma unroll
@@ -346,17 +354,24 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
         for (int j = 0; j < TN; ++j) bf[j] = b_s[roff_b[q] + j * 32 * CHUNKS];
     };
 
-    if (it_end > it_begin) {
-        gload(it_begin);
-        sstore(0);
+    const int nslab = it_end - it_begin;
+    if (nslab > 0) {
+        gload(it_begin, ra0, rb0);
+        sstore(0, ra0, rb0);
+        if (nslab > 1) gload(it_begin + 1, ra1, rb1);
     }
     __syncthreads();
-    for (int it = it_begin; it < it_end; ++it) {
+    // slab j = it - it_begin lives in LDS buffer j & 1 and was staged through register set j & 1
+    // `steady`: slabs it + 1 and it + 2 exist for sure, so the loads and the LDS stores are unconditional
+    // (every path through the steady loop then has the same loads in flight, which lets the compiler
+    // wait for exactly the older set before the stores).
+    auto step = [&](int it, const bool steady, uint4 (&ra_cur)[NCA], uint4 (&rb_cur)[NCB], const uint4 (&ra_nxt)[NCA],
+                    const uint4 (&rb_nxt)[NCB]) __attribute__((always_inline)) {
         const int buf = (it - it_begin) & 1;
-        if (it + 1 < it_end) gload(it + 1);
+        if (steady || it + 2 < it_end) gload(it + 2, ra_cur, rb_cur);
         const uint4* a_s = smem + buf * STAGE;
         const uint4* b_s = a_s + BM * CHUNKS;
-        // the small tile keeps two sets of fragments in flight; the large one has no registers to spare
+        // the 64x64 wave tile keeps two sets of fragments in flight
         constexpr int NF = (TM * TN <= 4) ? 2 : 1;
         uint4 af[NF][TM], bf[NF][TN];
         if (NF == 2) lfrag(a_s, b_s, 0, af[0], bf[0]);
@@ -373,8 +388,17 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
                 for (int i = 0; i < NRS; ++i) mma<TI>(rs[i], af[q % NF][i], ones);
             }
         }
-        if (it + 1 < it_end) sstore(buf ^ 1);
+        if (steady || it + 1 < it_end) sstore(buf ^ 1, ra_nxt, rb_nxt);
         __syncthreads();
+    };
+    int it = it_begin;
+    for (; it + 3 < it_end; it += 2) {
+        step(it, true, ra0, rb0, ra1, rb1);
+        step(it + 1, true, ra1, rb1, ra0, rb0);
+    }
+    for (; it < it_end; it += 2) {                        // the last one to three slabs
+        step(it, false, ra0, rb0, ra1, rb1);
+        if (it + 1 < it_end) step(it + 1, false, ra1, rb1, ra0, rb0);
     }
 
     if (RS && do_rs && (lane & 31) == 0) {
@@ -408,7 +432,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(Params P) {
     TO* C = static_cast<TO*>(P.C) + z * P.sC;
     const TI* bias = P.bias ? static_cast<const TI*>(P.bias) + z * P.sBias : nullptr;
     const float* add = P.add ? P.add + z * P.sAdd : nullptr;
-    if constexpr (FAST && TM == 2 && TN == 2) {
+    if constexpr (FAST && TM == 2 && TN == 2 && WN == 2) {
         // Full 128x128 tile: stage it through LDS (free after the loop's last barrier) so that every
         // store instruction writes whole rows of the tile, 16 bytes (float) or 8 bytes (bf16) per lane.
         // 16-byte column groups are XOR-swizzled with the row so both sides spread over the banks.
@@ -505,38 +529,43 @@ int fast_flags(const void* p, long long ld, long long stride, int batch, bool ro
     return f;
 }
 
-template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, bool FAST, bool RS>
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS>
 hipError_t launch_kernel(const Params& P, dim3 grid, hipStream_t stream) {
-    constexpr size_t lds = 2 * (size_t)(64 * TM + 64 * TN) * CHUNKS * 16;
+    constexpr size_t lds = 2 * (size_t)(64 * TM + 32 * TN * WN) * CHUNKS * 16;
     static thread_local bool attr_set = false;
     if (!attr_set && lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TI, TO, AT, BT, TM, TN, FAST, RS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<TI, TO, AT, BT, TM, TN, FAST, RS>), grid, dim3(NTHREADS), lds, stream, P);
+    hipLaunchKernelGGL((gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS>), grid, dim3(128 * WN), lds, stream, P);
     return hipGetLastError();
 }
 
-template <typename TI, typename TO, bool AT, bool BT, int TM, int TN>
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN>
 hipError_t launch_shape(const Params& P, bool fast, dim3 grid, hipStream_t stream) {
-    if constexpr (AT && BT && TM == 2 && TN == 2) {
-        if (P.rowsum)
-            return fast ? launch_kernel<TI, TO, AT, BT, TM, TN, true, true>(P, grid, stream)
-                        : launch_kernel<TI, TO, AT, BT, TM, TN, false, true>(P, grid, stream);
+    if constexpr (WN != 2) {
+        if (P.rowsum || !fast) return hipErrorInvalidValue;   // the large tile is built unguarded and without row sums
+        return launch_kernel<TI, TO, AT, BT, TM, TN, WN, true, false>(P, grid, stream);
+    } else {
+        if constexpr (AT && BT) {
+            if (P.rowsum)
+                return fast ? launch_kernel<TI, TO, AT, BT, TM, TN, WN, true, true>(P, grid, stream)
+                            : launch_kernel<TI, TO, AT, BT, TM, TN, WN, false, true>(P, grid, stream);
+        }
+        if (P.rowsum) return hipErrorInvalidValue;           // row sums exist for the dA^T X form on 128x128 tiles only
+        return fast ? launch_kernel<TI, TO, AT, BT, TM, TN, WN, true, false>(P, grid, stream)
+                    : launch_kernel<TI, TO, AT, BT, TM, TN, WN, false, false>(P, grid, stream);
     }
-    if (P.rowsum) return hipErrorInvalidValue;           // row sums exist for the dA^T X form on 128x128 tiles only
-    return fast ? launch_kernel<TI, TO, AT, BT, TM, TN, true, false>(P, grid, stream)
-                : launch_kernel<TI, TO, AT, BT, TM, TN, false, false>(P, grid, stream);
 }
 
-template <typename TI, typename TO, int TM, int TN>
+template <typename TI, typename TO, int TM, int TN, int WN>
 hipError_t launch_form(const GemmDesc& d, const Params& P, bool fast, dim3 grid, hipStream_t stream) {
-    if (!d.atrans && !d.btrans) return launch_shape<TI, TO, false, false, TM, TN>(P, fast, grid, stream);
-    if (!d.atrans && d.btrans) return launch_shape<TI, TO, false, true, TM, TN>(P, fast, grid, stream);
-    if (d.atrans && d.btrans) return launch_shape<TI, TO, true, true, TM, TN>(P, fast, grid, stream);
-    return launch_shape<TI, TO, true, false, TM, TN>(P, fast, grid, stream);
+    if (!d.atrans && !d.btrans) return launch_shape<TI, TO, false, false, TM, TN, WN>(P, fast, grid, stream);
+    if (!d.atrans && d.btrans) return launch_shape<TI, TO, false, true, TM, TN, WN>(P, fast, grid, stream);
+    if (d.atrans && d.btrans) return launch_shape<TI, TO, true, true, TM, TN, WN>(P, fast, grid, stream);
+    return launch_shape<TI, TO, true, false, TM, TN, WN>(P, fast, grid, stream);
 }
 
 // The unguarded kernel applies when every tile is full, every segment's K is a whole number of
@@ -575,7 +604,8 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
         P.c_vec = aligned(d.C, w) && d.ldc % 4 == 0 && ((d.batch > 1 ? d.sC : 0) % 4 == 0);
     }
     const int batch = d.batch > 0 ? d.batch : 1;
-    const GemmPlan plan = plan_gemm(d);
+    GemmPlan plan = plan_gemm(d);
+    if (plan.big_tile && !can_run_fast<TI>(d, P, 256)) plan.big_tile = false;   // the large tile has no guarded form
     const int tile = plan.big_tile ? 256 : 128;
     P.ntm = (d.M + tile - 1) / tile; P.ntn = (d.N + tile - 1) / tile;
     P.splits = plan.splits;
@@ -586,7 +616,7 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     hipError_t e;
     if (plan.splits > 1) {
         // partial tiles are float whatever the output type
-        e = plan.big_tile ? launch_form<TI, float, 4, 4>(d, P, fast, grid, stream) : launch_form<TI, float, 2, 2>(d, P, fast, grid, stream);
+        e = plan.big_tile ? launch_form<TI, float, 4, 2, 4>(d, P, fast, grid, stream) : launch_form<TI, float, 2, 2, 2>(d, P, fast, grid, stream);
         if (e != hipSuccess) return e;
         const long long total = (long long)d.M * d.N;
         unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
@@ -595,7 +625,7 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
                            P.rs_partial, d.rowsum, d.sRowsum);
         return hipGetLastError();
     }
-    return plan.big_tile ? launch_form<TI, TO, 4, 4>(d, P, fast, grid, stream) : launch_form<TI, TO, 2, 2>(d, P, fast, grid, stream);
+    return plan.big_tile ? launch_form<TI, TO, 4, 2, 4>(d, P, fast, grid, stream) : launch_form<TI, TO, 2, 2, 2>(d, P, fast, grid, stream);
 }
 
 }  // namespace
@@ -609,14 +639,21 @@ GemmPlan plan_gemm(const GemmDesc& d) {
     // when the contraction is long enough to amortise them
     int ktot = 0;
     for (int s = 0; s < d.nseg; ++s) ktot += d.seg[s].K;
-    if (t256 >= 1024 && !d.rowsum && ktot >= 512) { p.big_tile = true; return p; }
-    // few output tiles and a long contraction: split K so that about 256 workgroups are in flight
-    if (d.nseg == 1 && !d.add && d.partial && t128 <= 128) {
+    if (t256 >= 512 && !d.rowsum && ktot >= 512) { p.big_tile = true; return p; }
+    // Few output tiles and a long contraction: split K.  Up to one workgroup per CU whenever each part
+    // keeps at least 8 slabs; up to two per CU (the number that fit) when each part keeps at least 64,
+    // so that the float partial tiles and the reduction stay small next to the product itself.
+    if (d.nseg == 1 && !d.add && d.partial && t128 <= 256) {
         const int bk = d.in_type == DT_BF16 ? 64 : 32;
         const int slabs = (d.seg[0].K + bk - 1) / bk;
-        int s = (int)(256 / t128);
-        if (s > 8) s = 8;
-        while (s > 1 && slabs / s < 8) --s;
+        auto parts = [&](long long target, int min_slabs) {
+            int s = (int)(target / t128);
+            if (s > 8) s = 8;
+            while (s > 1 && slabs / s < min_slabs) --s;
+            return s < 1 ? 1 : s;
+        };
+        const int s1 = parts(256, 8), s2 = parts(512, 64);
+        const int s = s1 > s2 ? s1 : s2;
         const size_t need = (size_t)s * batch * ((size_t)d.M * d.N + d.M) * sizeof(float);
         if (s > 1 && need <= d.partial_bytes) {
             p.splits = s;
