@@ -204,7 +204,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
     c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false;
     c->wUHT = w; c->wCNT = w;
-    if (c->st == DT_BF16 && rec_waves_for(c->H) > 0) {
+    if (c->st == DT_BF16 && rec_waves_for(c->H, c->B) > 0) {
         const int NU = c->H / 32, tiles = (c->B + 31) / 32;
         int nbg = 256 / (2 * NU);
         if (nbg > tiles) nbg = tiles;

@@ -35,8 +35,14 @@ __device__ __forceinline__ float tanhf_(float a) { return tanhf(a); }
 
 // Hardware exp2/rcp forms for the bf16 path: absolute error of a few 1e-7, far below the
 // 2^-9 relative step of the bf16 values they feed; both saturate cleanly for large |a|.
-__device__ __forceinline__ float fast_sigmoid(float a) { return __frcp_rn(1.0f + __expf(-a)); }
-__device__ __forceinline__ float fast_tanh(float a) { return 1.0f - 2.0f * __frcp_rn(__expf(2.0f * a) + 1.0f); }
+// (v_exp_f32 and v_rcp_f32 directly: 1 ulp each, no range fix-ups; exp2 underflows to 0 and
+// overflows to +inf, which the reciprocal maps to the right limits.)
+__device__ __forceinline__ float fast_sigmoid(float a) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * a));
+}
+__device__ __forceinline__ float fast_tanh(float a) {
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(2.88539008f * a) + 1.0f);
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

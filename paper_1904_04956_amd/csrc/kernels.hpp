@@ -60,7 +60,7 @@ struct RecBwdArgs {
     int T, B, H, nbg, tiles_per_group;
 };
 // Wavefronts per workgroup of the persistent kernels for this H, 0 if H is not supported.
-int rec_waves_for(int H);
+int rec_waves_for(int H, int B);
 // *launched is false (and nothing was enqueued) when the grid cannot be co-resident on this device.
 hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bool* launched);
 hipError_t launch_rec_bwd(const RecBwdArgs& a, bool sentinel, hipStream_t st, bool* launched);

@@ -2,7 +2,8 @@
 //
 // A workgroup owns 32 hidden units of one direction (all four gate rows of each) and a group
 // of 32-row batch tiles.  Its slice of U_h stays in vector registers for the whole launch:
-// NW wavefronts split the contraction index, each holding 128 VGPRs of MFMA B-fragments.
+// NW wavefronts split the contraction index, each holding its part as MFMA B-fragments (64 to 256
+// VGPRs per lane, by width).
 // Per frame and batch tile a workgroup multiplies the previous h (forward) or the previous
 // frame's gate gradients (backward) by its slice, reduces the NW partial accumulators through
 // LDS, applies the cell arithmetic with all four gates of a unit in one lane, and writes its
@@ -72,9 +73,12 @@ __device__ __forceinline__ uint4 ld_coh_16B(const bf16_t* p) {
     const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
 }
-__device__ __forceinline__ bool has_sentinel(unsigned w) { return (w & 0xFFFFu) == SENT16 || (w >> 16) == SENT16; }
-__device__ __forceinline__ bool has_sentinel(const uint4& v) {
-    return has_sentinel(v.x) || has_sentinel(v.y) || has_sentinel(v.z) || has_sentinel(v.w);
+// Nonzero iff one of the two bf16 halves of w is 0xFFFF: the zero-halfword test on ~w, branch-free
+// (the chunks are checked on every frame, so the test is a few ALU operations per word and one
+// comparison per wave, not a chain of branches).
+__device__ __forceinline__ unsigned sentinel_bits(unsigned w) { return (~w - 0x00010001u) & w & 0x80008000u; }
+__device__ __forceinline__ unsigned sentinel_bits(const uint4& v) {
+    return sentinel_bits(v.x) | sentinel_bits(v.y) | sentinel_bits(v.z) | sentinel_bits(v.w);
 }
 
 // Bounded wait of one wave.  `probe` points, for the lanes with probing set, at one element of each
@@ -106,10 +110,10 @@ __device__ __forceinline__ void load_chunks(uint4 (&frag)[NQ], const bf16_t* p, 
 }
 template <int NQ>
 __device__ __forceinline__ bool all_written(const uint4 (&frag)[NQ]) {
-    bool ok = true;
+    unsigned m = 0;
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) ok = ok && !has_sentinel(frag[q]);
-    return __all(ok);
+    for (int q = 0; q < NQ; ++q) m |= sentinel_bits(frag[q]);
+    return __all(m == 0);
 }
 // The chunks in frag were loaded once; reloads them until no element of any lane is the sentinel
 // (or the wait is abandoned).  Normally the first check passes.
@@ -179,13 +183,15 @@ __device__ __forceinline__ int tiles_in_batch(int bg, int tiles_per_group, int B
 
 // ------------------------------------------------------------------------------ forward
 // KW = contraction elements per wavefront: H = NW * KW.
-template <int NW, int KW, bool SENTINEL>
+// FULL: B is a multiple of 32, so every row of every tile exists and no access is predicated.
+template <int NW, int KW, bool SENTINEL, bool FULL>
 __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     constexpr int EPT = 16 / NW;                         // accumulator registers (batch rows) per thread
     constexpr int KSTEPS = KW / 16;                      // MFMA steps per gate per wavefront
     extern __shared__ float lds[];                       // [NW][4][4][64][4] partial accumulators
-    const int H = a.H, B = a.B, T = a.T;
-    const int NU = H / 32;
+    constexpr int H = NW * KW;                           // (the launcher picks NW and KW from a.H)
+    const int B = a.B, T = a.T;
+    constexpr int NU = H / 32;
     const GroupMap gm = map_block(NU, a.nbg);
     const int d = gm.d, u = gm.u;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -207,6 +213,15 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     const int j = u * 32 + l32;                          // this thread's hidden unit
     float4* l4 = reinterpret_cast<float4*>(lds);
 
+    // Addresses are a per-item uniform base (frame and tile origin) plus per-thread 32-bit element
+    // offsets computed once: brow[e] is the batch row of accumulator register e within a tile.
+    // Register e is batch row rb + re(e) of the tile: rb per thread, re(e) a compile-time constant.
+    const int rb = 2 * EPT * wave + 4 * lh;
+    auto re = [](int e) { return 8 * (e >> 2) + (e & 3); };
+    const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // into [.][2H] tensors (h, c)
+    const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // into [.][8H] tensors (a_x, gates)
+    const unsigned ohp = (unsigned)(l32 * 2 * H + d * H + wave * KW + 8 * lh);   // A-fragment chunks of h: row l32
+
     // Per-item inputs that do not depend on the exchange (a_x of the frame, previous cell state) are
     // loaded one item ahead, so that their HBM latency never sits on the frame-to-frame path.
     // Item = (visited frame n, batch tile i); this thread's EPT batch rows are accumulator
@@ -216,15 +231,14 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         const int t = d ? T - 1 - n : n;
         const int tp = d ? T - n : n - 1;
         const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
+        const float* axb = a.ax + ((size_t)t * B + b0) * 8 * H;
+        const float* cpb = a.c + ((size_t)(n > 0 ? tp : t) * B + b0) * 2 * H;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            const int r = EPT * wave + e;
-            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            const bool ok = b < B;
-            const float* p = a.ax + ((size_t)t * B + (ok ? b : 0)) * 8 * H + (size_t)d * 4 * H + j;
+            const bool ok = FULL || b0 + rb + re(e) < B;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) ax[e][g] = ok ? p[(size_t)g * H] : 0.0f;
-            cp[e] = (ok && n > 0) ? a.c[((size_t)tp * B + b) * 2 * H + (size_t)d * H + j] : 0.0f;
+            for (int g = 0; g < 4; ++g) ax[e][g] = ok ? axb[o8b + (unsigned)((re(e) * 8 + g) * H)] : 0.0f;
+            cp[e] = (ok && n > 0) ? cpb[o2b + (unsigned)(re(e) * 2 * H)] : 0.0f;
         }
     };
 
@@ -249,13 +263,14 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         if (n > 0) {
             // previous h of this batch tile: row l32, 8 consecutive k per lane
             const int row = b0 + l32;
-            const bool valid = row < B;
-            const bf16_t* hp = a.y + ((size_t)tp * B + (valid ? row : 0)) * 2 * H + (size_t)d * H + wave * KW + 8 * lh;
+            const bool valid = FULL || row < B;
+            const bf16_t* hb = a.y + ((size_t)tp * B + b0) * 2 * H;       // uniform: previous frame, this tile
+            const bf16_t* hp = hb + (valid ? ohp : ohp - (unsigned)(l32 * 2 * H));
             uint4 afrag[KSTEPS];
             if (SENTINEL) {
                 // one probe per producing workgroup of this wavefront's k-range: its last unit, last valid row
-                const int prow = min(b0 + 31, B - 1);
-                const bf16_t* probe = a.y + ((size_t)tp * B + prow) * 2 * H + (size_t)d * H + wave * KW + (lane & (KW / 32 - 1)) * 32 + 31;
+                const int prow = FULL ? b0 + 31 : min(b0 + 31, B - 1);
+                const bf16_t* probe = hb + (unsigned)((prow - b0) * 2 * H + d * H + wave * KW + (lane & (KW / 32 - 1)) * 32 + 31);
                 bool got = false, gu = false;
                 if (have_pre) {
 #pragma unroll
@@ -289,9 +304,10 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             if (SENTINEL && KW == 128 && ntl >= 2 && item + 1 < nitems) {
                 const int n2 = (item + 1) / ntl, i2 = (item + 1) - n2 * ntl;
                 const int tp2 = d ? T - n2 : n2 - 1;
-                const int row2 = (gm.bg * a.tiles_per_group + i2) * 32 + l32;
-                const bool valid2 = row2 < B;
-                load_chunks_cached<KSTEPS>(apre, a.y + ((size_t)tp2 * B + (valid2 ? row2 : 0)) * 2 * H + (size_t)d * H + wave * KW + 8 * lh, valid2);
+                const int b02 = (gm.bg * a.tiles_per_group + i2) * 32;
+                const bool valid2 = FULL || b02 + l32 < B;
+                const bf16_t* hb2 = a.y + ((size_t)tp2 * B + b02) * 2 * H;
+                load_chunks_cached<KSTEPS>(apre, hb2 + (valid2 ? ohp : ohp - (unsigned)(l32 * 2 * H)), valid2);
                 have_pre = true;
             }
             // partial accumulators -> LDS as [wave][gate][reg/4][lane][reg%4]
@@ -325,33 +341,31 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         }
         // cell arithmetic; h goes out first because it is all the other workgroups wait for
         float gi[EPT], gf[EPT], gg[EPT], go[EPT], cn[EPT];
+        bf16_t* yb = a.y + ((size_t)t * B + b0) * 2 * H;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            const int r = EPT * wave + e;
-            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
             gi[e] = fast_sigmoid(ax[e][0] + sum[e][0]);
             gf[e] = fast_sigmoid(ax[e][1] + sum[e][1]);
             gg[e] = fast_tanh(ax[e][2] + sum[e][2]);
             go[e] = fast_sigmoid(ax[e][3] + sum[e][3]);
             cn[e] = gf[e] * cp[e] + gi[e] * gg[e];
             const float h = go[e] * fast_tanh(cn[e]);
-            if (b < B) {
-                bf16_t* yp = a.y + ((size_t)t * B + b) * 2 * H + (size_t)d * H + j;
+            if (FULL || b0 + rb + re(e) < B) {
+                bf16_t* yp = yb + (o2b + (unsigned)(re(e) * 2 * H));
                 if (SENTINEL) st_coh_bf16(yp, h); else *yp = f2bf(h);
             }
         }
         if (SENTINEL) lds_barrier();                     // frees the LDS buffer for the next item
         else signal_counter(cnt + i);                    // barrier inside: same role
         // saved for the backward pass only: off the critical path of the exchange
+        float* cb = a.c + ((size_t)t * B + b0) * 2 * H;
+        bf16_t* gb = a.gates + ((size_t)t * B + b0) * 8 * H;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            const int r = EPT * wave + e;
-            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            if (b < B) {
-                const size_t m = (size_t)t * B + b;
-                a.c[m * 2 * H + (size_t)d * H + j] = cn[e];
-                bf16_t* gp = a.gates + m * 8 * H + (size_t)d * 4 * H + j;
-                gp[0] = f2bf(gi[e]); gp[(size_t)H] = f2bf(gf[e]); gp[(size_t)2 * H] = f2bf(gg[e]); gp[(size_t)3 * H] = f2bf(go[e]);
+            if (FULL || b0 + rb + re(e) < B) {
+                cb[o2b + (unsigned)(re(e) * 2 * H)] = cn[e];
+                bf16_t* gp = gb + (o8b + (unsigned)(re(e) * 8 * H));
+                gp[0] = f2bf(gi[e]); gp[(unsigned)H] = f2bf(gf[e]); gp[(unsigned)(2 * H)] = f2bf(gg[e]); gp[(unsigned)(3 * H)] = f2bf(go[e]);
             }
         }
         // next item's inputs; with one tile per workgroup its previous cell state is the one just computed
@@ -365,18 +379,19 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------ backward
-template <int NW, int KW, bool SENTINEL>
+template <int NW, int KW, bool SENTINEL, bool FULL>
 __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     constexpr int EPT = 16 / NW;
     constexpr int KSTEPS = 4 * KW / 16;                  // the contraction runs over the 4H gate rows
     extern __shared__ float lds[];                       // [NW][4][64][4]
-    const int H = a.H, B = a.B, T = a.T;
-    const int NU = H / 32;
+    constexpr int H = NW * KW;                           // (the launcher picks NW and KW from a.H)
+    const int B = a.B, T = a.T;
+    constexpr int NU = H / 32;
     const GroupMap gm = map_block(NU, a.nbg);
     const int d = gm.d, u = gm.u;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
-    const int KWB = 4 * H / NW;                          // gate rows per wavefront (= 4 * KW)
+    constexpr int KWB = 4 * H / NW;                         // gate rows per wavefront (= 4 * KW)
     const int ntl = tiles_in_batch(gm.bg, a.tiles_per_group, B);
     if (ntl == 0) return;
 
@@ -392,6 +407,14 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     const int j = u * 32 + l32;
     float4* l4 = reinterpret_cast<float4*>(lds);
 
+    // per-thread 32-bit element offsets, added to per-item uniform bases (as in the forward kernel)
+    const int rb = 2 * EPT * wave + 4 * lh;              // register e is batch row rb + re(e) of the tile
+    auto re = [](int e) { return 8 * (e >> 2) + (e & 3); };
+    const unsigned o1b = (unsigned)(rb * H + j);                 // into [.][H] (carried dE/dc),
+    const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // [.][2H] (c, dy)
+    const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // and [.][8H] tensors (gates, dE/da)
+    const unsigned oap = (unsigned)(l32 * 8 * H + d * 4 * H + wave * KWB + 8 * lh);   // A-fragment chunks of dE/da: row l32
+
     // Saved activations of an item, loaded one item ahead (raw bf16 for the gates and dy).
     struct Inputs { bf16_t g[EPT][4]; bf16_t dy[EPT]; float c[EPT], cp[EPT], dcr[EPT]; };
     auto issue_inputs = [&](int item, Inputs& in) {
@@ -400,32 +423,32 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         const int t = d ? T - 1 - n : n;
         const int tp = d ? T - n : n - 1;
         const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
+        const size_t m0 = (size_t)t * B + b0;
+        const bf16_t* gb = a.gates + m0 * 8 * H;
+        const float* cb = a.c + m0 * 2 * H;
+        const float* cpb = a.c + ((size_t)(n > 0 ? tp : t) * B + b0) * 2 * H;
+        const bf16_t* dyb = a.dy + m0 * 2 * H;
+        const float* dcb = a.dc + ((size_t)d * B + b0) * H;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            const int r = EPT * wave + e;
-            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            const bool ok = b < B;
-            const size_t m = (size_t)t * B + (ok ? b : 0);
-            const bf16_t* gp = a.gates + m * 8 * H + (size_t)d * 4 * H + j;
+            const bool ok = FULL || b0 + rb + re(e) < B;
+            const unsigned o2 = o2b + (unsigned)(re(e) * 2 * H);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) in.g[e][g] = ok ? gp[(size_t)g * H] : (bf16_t)0;
-            in.c[e] = ok ? a.c[m * 2 * H + (size_t)d * H + j] : 0.0f;
-            in.cp[e] = (ok && n > 0) ? a.c[((size_t)tp * B + b) * 2 * H + (size_t)d * H + j] : 0.0f;
-            in.dy[e] = ok ? a.dy[m * 2 * H + (size_t)d * H + j] : (bf16_t)0;
-            in.dcr[e] = (ok && n < T - 1) ? a.dc[((size_t)d * B + b) * H + j] : 0.0f;
+            for (int g = 0; g < 4; ++g) in.g[e][g] = ok ? gb[o8b + (unsigned)((re(e) * 8 + g) * H)] : (bf16_t)0;
+            in.c[e] = ok ? cb[o2] : 0.0f;
+            in.cp[e] = (ok && n > 0) ? cpb[o2] : 0.0f;
+            in.dy[e] = ok ? dyb[o2] : (bf16_t)0;
+            in.dcr[e] = (ok && n < T - 1) ? dcb[o1b + (unsigned)(re(e) * H)] : 0.0f;
         }
     };
 
-    // With 16 rows per thread (one wavefront per workgroup) two sets of inputs do not fit in
-    // registers: that variant loads each item's inputs at the item's start instead.
-    constexpr bool AHEAD = EPT <= 8;
+    static_assert(EPT <= 8, "two sets of inputs (this item's and the next one's) must fit in registers");
     const int nitems = T * ntl;
     Inputs cur;
-    if (AHEAD) issue_inputs(0, cur);
+    issue_inputs(0, cur);
     uint4 apre[8];                                       // first slab of the next item, loaded ahead (several tiles only)
     bool have_pre = false;
     for (int item = 0; item < nitems; ++item) {
-        if (!AHEAD) issue_inputs(item, cur);
         const int ni = item / ntl, i = item - ni * ntl;
         const int n = T - 1 - ni;
         const int t = d ? T - 1 - n : n;
@@ -437,16 +460,17 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         for (int e = 0; e < EPT; ++e) dh[e] = 0.0f;
         if (n < T - 1) {
             const int row = b0 + l32;
-            const bool valid = row < B;
-            const bf16_t* ap = a.da + ((size_t)tn * B + (valid ? row : 0)) * 8 * H + (size_t)d * 4 * H + wave * KWB + 8 * lh;
+            const bool valid = FULL || row < B;
+            const bf16_t* ab = a.da + ((size_t)tn * B + b0) * 8 * H;      // uniform: the frame visited before, this tile
+            const bf16_t* ap = ab + (valid ? oap : oap - (unsigned)(l32 * 8 * H));
             f32x16_t acc;
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
             if (SENTINEL) {
                 // the gate rows of this wavefront come from KWB/32 producers: probe each one's last unit,
                 // then stream the slabs of 128 gate rows with the next slab's loads in flight
-                const int prow = min(b0 + 31, B - 1);
-                const bf16_t* probe = a.da + ((size_t)tn * B + prow) * 8 * H + (size_t)d * 4 * H + wave * KWB + (lane & (4 * KW / 32 - 1)) * 32 + 31;
+                const int prow = FULL ? b0 + 31 : min(b0 + 31, B - 1);
+                const bf16_t* probe = ab + (unsigned)((prow - b0) * 8 * H + d * 4 * H + wave * KWB + (lane & (4 * KW / 32 - 1)) * 32 + 31);
                 uint4 afrag[2][8];
                 bool got = false, gu = false;
                 if (have_pre) {
@@ -463,16 +487,17 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 for (int sl = 0; sl < KSTEPS / 8; ++sl) {
                     if (sl + 1 < KSTEPS / 8) load_chunks_cached<8>(afrag[(sl + 1) & 1], ap + (sl + 1) * 128, valid);
                     else {
-                        if (AHEAD && item + 1 < nitems) issue_inputs(item + 1, nxt);
+                        if (item + 1 < nitems) issue_inputs(item + 1, nxt);
                         have_pre = false;
                         if (KW == 128 && ntl >= 2 && item + 1 < nitems) {
                             const int ni2 = (item + 1) / ntl, i2 = (item + 1) - ni2 * ntl;
                             const int n2 = T - 1 - ni2;
                             if (n2 < T - 1) {
                                 const int tn2 = d ? T - 2 - n2 : n2 + 1;
-                                const int row2 = (gm.bg * a.tiles_per_group + i2) * 32 + l32;
-                                const bool valid2 = row2 < B;
-                                load_chunks_cached<8>(apre, a.da + ((size_t)tn2 * B + (valid2 ? row2 : 0)) * 8 * H + (size_t)d * 4 * H + wave * KWB + 8 * lh, valid2);
+                                const int b02 = (gm.bg * a.tiles_per_group + i2) * 32;
+                                const bool valid2 = FULL || b02 + l32 < B;
+                                const bf16_t* ab2 = a.da + ((size_t)tn2 * B + b02) * 8 * H;
+                                load_chunks_cached<8>(apre, ab2 + (valid2 ? oap : oap - (unsigned)(l32 * 8 * H)), valid2);
                                 have_pre = true;
                             }
                         }
@@ -489,7 +514,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
 #pragma unroll
                     for (int q = 0; q < 8; ++q)
                         afrag[q] = valid ? *reinterpret_cast<const uint4*>(ap + (q0 + q) * 16) : make_uint4(0, 0, 0, 0);
-                    if (AHEAD && q0 + 8 >= KSTEPS && item + 1 < nitems) issue_inputs(item + 1, nxt);
+                    if (q0 + 8 >= KSTEPS && item + 1 < nitems) issue_inputs(item + 1, nxt);
 #pragma unroll
                     for (int q = 0; q < 8; ++q) acc = mfma_bf16(afrag[q], bfrag[q0 + q], acc);
                 }
@@ -505,14 +530,13 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                     const int r = EPT * wave + e;
                     dh[e] += lds[(((w2 * 4 + (r >> 2)) * 64 + lane) << 2) + (r & 3)];
                 }
-        } else if (AHEAD && item + 1 < nitems) {
+        } else if (item + 1 < nitems) {
             issue_inputs(item + 1, nxt);
         }
         float dcf[EPT];
+        bf16_t* dab = a.da + ((size_t)t * B + b0) * 8 * H;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            const int r = EPT * wave + e;
-            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
             const float gi = bf2f(cur.g[e][0]), gf = bf2f(cur.g[e][1]), gg = bf2f(cur.g[e][2]), go = bf2f(cur.g[e][3]);
             const float dht = dh[e] + bf2f(cur.dy[e]);
             const float tc = fast_tanh(cur.c[e]);
@@ -522,31 +546,27 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
             const float da_f = dc * cur.cp[e] * gf * (1.0f - gf);
             const float da_g = dc * gi * (1.0f - gg * gg);
             dcf[e] = dc * gf;
-            if (b < B) {
-                bf16_t* dp = a.da + ((size_t)t * B + b) * 8 * H + (size_t)d * 4 * H + j;
+            if (FULL || b0 + rb + re(e) < B) {
+                bf16_t* dp = dab + (o8b + (unsigned)(re(e) * 8 * H));
                 if (SENTINEL) {
-                    st_coh_bf16(dp, da_i); st_coh_bf16(dp + (size_t)H, da_f);
-                    st_coh_bf16(dp + (size_t)2 * H, da_g); st_coh_bf16(dp + (size_t)3 * H, da_o);
+                    st_coh_bf16(dp, da_i); st_coh_bf16(dp + (unsigned)H, da_f);
+                    st_coh_bf16(dp + (unsigned)(2 * H), da_g); st_coh_bf16(dp + (unsigned)(3 * H), da_o);
                 } else {
-                    dp[0] = f2bf(da_i); dp[(size_t)H] = f2bf(da_f); dp[(size_t)2 * H] = f2bf(da_g); dp[(size_t)3 * H] = f2bf(da_o);
+                    dp[0] = f2bf(da_i); dp[(unsigned)H] = f2bf(da_f); dp[(unsigned)(2 * H)] = f2bf(da_g); dp[(unsigned)(3 * H)] = f2bf(da_o);
                 }
             }
         }
         if (SENTINEL) lds_barrier();
         else signal_counter(cnt + i);
+        float* dcb = a.dc + ((size_t)d * B + b0) * H;
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const int r = EPT * wave + e;
-            const int b = b0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            if (b < B) a.dc[((size_t)d * B + b) * H + j] = dcf[e];
-        }
+        for (int e = 0; e < EPT; ++e)
+            if (FULL || b0 + rb + re(e) < B) dcb[o1b + (unsigned)(re(e) * H)] = dcf[e];
         // next item's inputs; with one tile per workgroup its carried dE/dc is the one just computed
-        if (AHEAD) {
-            cur = nxt;
-            if (ntl == 1) {
+        cur = nxt;
+        if (ntl == 1) {
 #pragma unroll
-                for (int e = 0; e < EPT; ++e) cur.dcr[e] = dcf[e];
-            }
+            for (int e = 0; e < EPT; ++e) cur.dcr[e] = dcf[e];
         }
     }
 }
@@ -593,35 +613,45 @@ hipError_t prepare(K kernel, int threads, size_t dyn_lds, int grid, bool* fits) 
     return hipSuccess;
 }
 
-template <int NW, int KW, bool S>
-hipError_t run_fwd(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
+template <int NW, int KW, bool S, bool FULL>
+hipError_t run_fwd_as(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
     const size_t lds = (size_t)NW * 4 * 4 * 64 * 16;
     bool fits = false;
-    hipError_t e = prepare(rec_fwd_kernel<NW, KW, S>, 64 * NW, lds, grid, &fits);
+    hipError_t e = prepare(rec_fwd_kernel<NW, KW, S, FULL>, 64 * NW, lds, grid, &fits);
     if (e != hipSuccess || !fits) return e;
-    hipLaunchKernelGGL((rec_fwd_kernel<NW, KW, S>), dim3(grid), dim3(64 * NW), lds, st, a);
+    hipLaunchKernelGGL((rec_fwd_kernel<NW, KW, S, FULL>), dim3(grid), dim3(64 * NW), lds, st, a);
+    *launched = true;
+    return hipGetLastError();
+}
+template <int NW, int KW, bool S>
+hipError_t run_fwd(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
+    return a.B % 32 == 0 ? run_fwd_as<NW, KW, S, true>(a, grid, st, launched) : run_fwd_as<NW, KW, S, false>(a, grid, st, launched);
+}
+template <int NW, int KW, bool S, bool FULL>
+hipError_t run_bwd_as(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
+    const size_t lds = (size_t)NW * 4 * 64 * 16;
+    bool fits = false;
+    hipError_t e = prepare(rec_bwd_kernel<NW, KW, S, FULL>, 64 * NW, lds, grid, &fits);
+    if (e != hipSuccess || !fits) return e;
+    hipLaunchKernelGGL((rec_bwd_kernel<NW, KW, S, FULL>), dim3(grid), dim3(64 * NW), lds, st, a);
     *launched = true;
     return hipGetLastError();
 }
 template <int NW, int KW, bool S>
 hipError_t run_bwd(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
-    const size_t lds = (size_t)NW * 4 * 64 * 16;
-    bool fits = false;
-    hipError_t e = prepare(rec_bwd_kernel<NW, KW, S>, 64 * NW, lds, grid, &fits);
-    if (e != hipSuccess || !fits) return e;
-    hipLaunchKernelGGL((rec_bwd_kernel<NW, KW, S>), dim3(grid), dim3(64 * NW), lds, st, a);
-    *launched = true;
-    return hipGetLastError();
+    return a.B % 32 == 0 ? run_bwd_as<NW, KW, S, true>(a, grid, st, launched) : run_bwd_as<NW, KW, S, false>(a, grid, st, launched);
 }
 
 }  // namespace
 
-// Supported widths: H = 128, 256, 512 (one, two, four wavefronts with 128 contraction elements each)
-// and H = 1024 (four wavefronts with 256 each: the U_h slice then fills 256 registers per lane).
-int rec_waves_for(int H) {
-    if (H == 128) return 1;
-    if (H == 256) return 2;
-    if (H == 512 || H == 1024) return 4;
+// Supported widths: H = 128 (two wavefronts with 64 contraction elements each), 256 and 512 (two and
+// four wavefronts with 128 each) and 1024 (four wavefronts with 256 each: the U_h slice then fills 256
+// registers per lane, which leaves no room for the predicates of a ragged batch, so that width
+// needs B to be a multiple of 32).  Returns the wavefronts per workgroup, 0 if unsupported.
+int rec_waves_for(int H, int B) {
+    if (H == 128 || H == 256) return 2;
+    if (H == 512) return 4;
+    if (H == 1024 && B % 32 == 0) return 4;
     return 0;
 }
 
@@ -650,10 +680,12 @@ hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bo
     *launched = false;
     const int grid = 2 * a.nbg * (a.H / 32);
     switch (a.H) {
-        case 128: return sentinel ? run_fwd<1, 128, true>(a, grid, st, launched) : run_fwd<1, 128, false>(a, grid, st, launched);
+        case 128: return sentinel ? run_fwd<2, 64, true>(a, grid, st, launched) : run_fwd<2, 64, false>(a, grid, st, launched);
         case 256: return sentinel ? run_fwd<2, 128, true>(a, grid, st, launched) : run_fwd<2, 128, false>(a, grid, st, launched);
         case 512: return sentinel ? run_fwd<4, 128, true>(a, grid, st, launched) : run_fwd<4, 128, false>(a, grid, st, launched);
-        case 1024: return sentinel ? run_fwd<4, 256, true>(a, grid, st, launched) : run_fwd<4, 256, false>(a, grid, st, launched);
+        case 1024:
+            if (a.B % 32 != 0) return hipSuccess;
+            return sentinel ? run_fwd_as<4, 256, true, true>(a, grid, st, launched) : run_fwd_as<4, 256, false, true>(a, grid, st, launched);
         default: return hipSuccess;
     }
 }
@@ -662,10 +694,12 @@ hipError_t launch_rec_bwd(const RecBwdArgs& a, bool sentinel, hipStream_t st, bo
     *launched = false;
     const int grid = 2 * a.nbg * (a.H / 32);
     switch (a.H) {
-        case 128: return sentinel ? run_bwd<1, 128, true>(a, grid, st, launched) : run_bwd<1, 128, false>(a, grid, st, launched);
+        case 128: return sentinel ? run_bwd<2, 64, true>(a, grid, st, launched) : run_bwd<2, 64, false>(a, grid, st, launched);
         case 256: return sentinel ? run_bwd<2, 128, true>(a, grid, st, launched) : run_bwd<2, 128, false>(a, grid, st, launched);
         case 512: return sentinel ? run_bwd<4, 128, true>(a, grid, st, launched) : run_bwd<4, 128, false>(a, grid, st, launched);
-        case 1024: return sentinel ? run_bwd<4, 256, true>(a, grid, st, launched) : run_bwd<4, 256, false>(a, grid, st, launched);
+        case 1024:
+            if (a.B % 32 != 0) return hipSuccess;
+            return sentinel ? run_bwd_as<4, 256, true, true>(a, grid, st, launched) : run_bwd_as<4, 256, false, true>(a, grid, st, launched);
         default: return hipSuccess;
     }
 }
