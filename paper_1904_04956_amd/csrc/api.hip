@@ -58,14 +58,14 @@ struct blstm_ctx {
     size_t off_wp, off_bp, off_ws, off_bs;
     // workspace (byte offsets)
     std::vector<size_t> wY, wG, wC;
-    size_t wAX, wPRE, wDA[2], wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, wPART2, wYend, part_bytes, part2_bytes, ws_bytes;
+    size_t wAX, wPRE, wDA[2], wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, wPART2, wHX, wDAX, hx_bytes, dax_bytes, part_bytes, part2_bytes, ws_bytes;
     int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
     int overlap;              // weight-gradient products on a second stream beside the next layer's recurrence: 0 never, 1 always, 2 by shape
     hipStream_t side;         // created on first use
-    hipEvent_t ev_fork, ev_da[2], ev_wg[2], ev_join;
+    hipEvent_t ev_fork, ev_da[2], ev_wg[2], ev_join, ev_fill;
     bool side_ready;
     char* ws;
     size_t ws_bound;
@@ -132,7 +132,7 @@ hipError_t ensure_side(blstm_ctx* c) {
     if (c->side_ready) return hipSuccess;
     hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e != hipSuccess) return e;
-    hipEvent_t* evs[6] = {&c->ev_fork, &c->ev_join, &c->ev_da[0], &c->ev_da[1], &c->ev_wg[0], &c->ev_wg[1]};
+    hipEvent_t* evs[7] = {&c->ev_fork, &c->ev_join, &c->ev_da[0], &c->ev_da[1], &c->ev_wg[0], &c->ev_wg[1], &c->ev_fill};
     for (hipEvent_t* ev : evs) {
         e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
         if (e != hipSuccess) return e;
@@ -185,8 +185,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     // workspace layout
     const size_t M = (size_t)c->M, B = (size_t)c->B, e = c->esz;
     size_t w = 0;
-    for (int l = 0; l < c->L; ++l) { c->wY.push_back(w); w += up256(M * 2 * H * e); }   // contiguous: one fill covers all
-    c->wYend = w;
+    for (int l = 0; l < c->L; ++l) { c->wY.push_back(w); w += up256(M * 2 * H * e); }
     for (int l = 0; l < c->L; ++l) {
         c->wG.push_back(w); w += up256(M * 8 * H * e);
         c->wC.push_back(w); w += up256(M * 2 * H * 4);
@@ -203,7 +202,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     c->wROWLOSS = w; w += up256(M * 4);
     // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
     c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false;
-    c->wUHT = w; c->wCNT = w;
+    c->wUHT = w; c->wCNT = w; c->wHX = w; c->wDAX = w; c->hx_bytes = 0; c->dax_bytes = 0;
     if (c->st == DT_BF16 && rec_waves_for(c->H, c->B) > 0) {
         const int NU = c->H / 32, tiles = (c->B + 31) / 32;
         int nbg = 256 / (2 * NU);
@@ -214,6 +213,13 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
         w += up256((size_t)c->L * 2 * 4 * H * H * 2);
         c->wCNT = w;
         w += up256(((size_t)2 * nbg * c->rec_tiles + 64) * 4);
+        // exchange copies of h and dE/da in MFMA-fragment order, one per layer (whole 32-row tiles),
+        // contiguous so that one fill marks all of a pass's copies as "not written yet"
+        const size_t Mx = (size_t)c->T * tiles * 32;
+        c->hx_bytes = up256(Mx * 2 * H * 2);
+        c->dax_bytes = up256(Mx * 8 * H * 2);
+        c->wHX = w;  w += c->hx_bytes * c->L;
+        c->wDAX = w; w += c->dax_bytes * c->L;
     }
     {   // split-K scratch: the largest need among the products with a small output
         const DType S = c->st;
@@ -248,7 +254,7 @@ void blstm_destroy(blstm_ctx* c) {
     if (!c) return;
     if (c->side_ready) {
         (void)hipStreamDestroy(c->side);
-        (void)hipEventDestroy(c->ev_fork); (void)hipEventDestroy(c->ev_join);
+        (void)hipEventDestroy(c->ev_fork); (void)hipEventDestroy(c->ev_join); (void)hipEventDestroy(c->ev_fill);
         for (int i = 0; i < 2; ++i) { (void)hipEventDestroy(c->ev_da[i]); (void)hipEventDestroy(c->ev_wg[i]); }
     }
     for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -301,7 +307,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
     ctx->have_forward = false;
     const bool persistent = ctx->rec_nbg > 0 && ctx->rec_path == 0;
     if (persistent && ctx->rec_sync == 1)    // h of every layer starts as "not written yet"
-        RUN(PC_MISC, "sentinel fill of h", launch_fill_bytes16(ctx->ws + ctx->wY[0], ctx->wYend - ctx->wY[0], 0xFFFFFFFFu, st));
+        RUN(PC_MISC, "sentinel fill of h", launch_fill_bytes16(ctx->ws + ctx->wHX, ctx->hx_bytes * ctx->L, 0xFFFFFFFFu, st));
     for (int l = 0; l < ctx->L; ++l) {
         const void* Xin = l == 0 ? x : static_cast<const void*>(ctx->ws + ctx->wY[l - 1]);
         const int Din = ctx->din(l);
@@ -328,7 +334,9 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
             RecFwdArgs a{};
             a.uh[0] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[0][l], e));
             a.uh[1] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[1][l], e));
-            a.ax = AX; a.y = reinterpret_cast<unsigned short*>(Y); a.gates = reinterpret_cast<unsigned short*>(G); a.c = C;
+            a.ax = AX; a.y = reinterpret_cast<unsigned short*>(Y);
+            a.hx = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wHX + ctx->hx_bytes * l);
+            a.gates = reinterpret_cast<unsigned short*>(G); a.c = C;
             a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
             bool launched = false;
@@ -462,16 +470,12 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
         ta.count = 2 * ctx->L;
         RUN(PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, st));
     }
-    // In sentinel mode each dE/da buffer starts a layer as "not written yet".  The fills run on the
-    // stream of the weight-gradient products (after the products that last read the buffer), so
-    // they stay off the recurrence's path; the first two are needed before anything else.
-    const size_t da_bytes = (size_t)M * 8 * H * e;
+    // In sentinel mode every layer's exchange copy of dE/da starts as "not written yet": one fill,
+    // on the stream of the weight-gradient products so that it runs beside the products at the top.
+    bool fill_pending = false;
     if (sentinel) {
-        for (int i = 0; i < 2 && i < ctx->L; ++i) {
-            const int db0 = (ctx->L - 1 - i) & 1;
-            RUN_ON(ws, PC_MISC, "sentinel fill of da", launch_fill_bytes16(ctx->ws + ctx->wDA[db0], da_bytes, 0xFFFFFFFFu, ws));
-            if (ov) { HIPCHK("fork", hipEventRecord(ctx->ev_wg[db0], ws)); wg_pending[db0] = true; }
-        }
+        RUN_ON(ws, PC_MISC, "sentinel fill of da", launch_fill_bytes16(ctx->ws + ctx->wDAX, ctx->dax_bytes * ctx->L, 0xFFFFFFFFu, ws));
+        if (ov) { HIPCHK("fork", hipEventRecord(ctx->ev_fill, ws)); fill_pending = true; }
     }
     const char* dY;
     int next_buf = 0;
@@ -509,6 +513,10 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             HIPCHK("buffer reuse", hipStreamWaitEvent(st, ctx->ev_wg[db], 0));
             wg_pending[db] = false;
         }
+        if (fill_pending) {
+            HIPCHK("fill", hipStreamWaitEvent(st, ctx->ev_fill, 0));
+            fill_pending = false;
+        }
         bool rec_done = false;
         if (ctx->rec_nbg > 0 && ctx->rec_path == 0) {
             unsigned* cnt = reinterpret_cast<unsigned*>(ctx->ws + ctx->wCNT);
@@ -521,6 +529,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             a.dy = reinterpret_cast<const unsigned short*>(dY);
             a.gates = reinterpret_cast<const unsigned short*>(G); a.c = C;
             a.da = reinterpret_cast<unsigned short*>(DA); a.dc = DC;
+            a.dax = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wDAX + ctx->dax_bytes * l);
             a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
             RUN(PC_REC_BWD, "persistent recurrent backward", launch_rec_bwd(a, ctx->rec_sync == 1, st, &rec_done));
@@ -584,13 +593,6 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             RUN(PC_GEMM_DGRAD, "dx", launch_gemm(d, st));
             dY = ctx->ws + ctx->wDY[next_buf];
             next_buf ^= 1;
-        }
-        if (sentinel && l >= 2) {                        // layer l-2 writes this buffer next: refill it once
-            if (ov) {                                    // both its readers (products above, dx) are done
-                HIPCHK("fork", hipEventRecord(ctx->ev_da[db], st));
-                HIPCHK("fork", hipStreamWaitEvent(ws, ctx->ev_da[db], 0));
-            }
-            RUN_ON(ws, PC_MISC, "sentinel fill of da", launch_fill_bytes16(DA, da_bytes, 0xFFFFFFFFu, ws));
         }
         if (ov) {
             HIPCHK("fork", hipEventRecord(ctx->ev_wg[db], ws));

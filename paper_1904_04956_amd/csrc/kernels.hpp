@@ -39,7 +39,8 @@ hipError_t launch_cell_bwd(const CellBwdArgs& a, DType store, hipStream_t s);
 struct RecFwdArgs {
     const unsigned short* uh[2];  // U_h per direction, [4H][H]
     const float* ax;              // W_x x + b for every frame, [M][8H]
-    unsigned short* y;            // layer output h, [M][2H]; pre-filled with 0xFFFF in sentinel mode
+    unsigned short* y;            // layer output h, [M][2H]
+    unsigned short* hx;           // h again in exchange order, [T][2][tiles][H/16][2][32][8]; pre-filled with 0xFFFF in sentinel mode
     unsigned short* gates;        // gate activations, [M][8H]
     float* c;                     // cell state, [M][2H]
     unsigned* cnt;                // [2*nbg][tiles_per_group] counters, zero before the launch
@@ -52,7 +53,8 @@ struct RecBwdArgs {
     const unsigned short* dy;     // dE/dh from above, [M][2H]
     const unsigned short* gates;  // [M][8H]
     const float* c;               // [M][2H]
-    unsigned short* da;           // dE/da, [M][8H]; pre-filled with 0xFFFF in sentinel mode
+    unsigned short* da;           // dE/da, [M][8H]
+    unsigned short* dax;          // dE/da again in exchange order, [T][2][tiles][4H/16][2][32][8]; pre-filled with 0xFFFF in sentinel mode
     float* dc;                    // carried dE/dc, [2][B][H]
     unsigned* cnt;
     unsigned* abort_word;

@@ -8,7 +8,13 @@
 // frame's gate gradients (backward) by its slice, reduces the NW partial accumulators through
 // LDS, applies the cell arithmetic with all four gates of a unit in one lane, and writes its
 // 32 columns.  The NU = H/32 workgroups that share a batch tile exchange these columns through
-// global memory, in one of two ways:
+// global memory.  The exchanged tensor is a copy kept in the order the consumers' MFMA A-fragments
+// want it, [frame][direction][32-row tile][16-column pair of chunks][chunk][row][8 columns]: a
+// wavefront's load of one fragment is then one contiguous KB (row-major storage makes the same
+// load touch 32 separate cache lines and runs three times slower), and a producer's 32 columns
+// of a tile are one contiguous 2 KB block.  The row-major tensors the products outside these
+// kernels read (h for the next layer, dE/da for the weight and input gradients) are written
+// as well, off the frame-to-frame path.  Two protocols order the exchange:
 //
 //   SENTINEL  The exchanged tensor (h, or dE/da) is filled with the bf16 bit pattern 0xFFFF (a
 //             NaN no finite value converts to) before the launch.  Producers store write-through
@@ -62,10 +68,12 @@ __device__ __forceinline__ void signal_counter(unsigned* cnt) {
 }
 
 // ---- SENTINEL protocol --------------------------------------------------------------------------
-__device__ __forceinline__ void st_coh_bf16(bf16_t* p, float v) {
+__device__ __forceinline__ bf16_t coh_bf16(float v) {
     bf16_t b = f2bf(v);
-    if (b == SENT16) b = 0x7FC0;                         // a NaN result must not look like "not written yet"
-    __hip_atomic_store(p, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return b == SENT16 ? (bf16_t)0x7FC0 : b;             // a NaN result must not look like "not written yet"
+}
+__device__ __forceinline__ void st_coh_bf16(bf16_t* p, float v) {
+    __hip_atomic_store(p, coh_bf16(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ uint4 ld_coh_16B(const bf16_t* p) {
     const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
@@ -73,13 +81,15 @@ __device__ __forceinline__ uint4 ld_coh_16B(const bf16_t* p) {
     const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
 }
-// Nonzero iff one of the two bf16 halves of w is 0xFFFF: the zero-halfword test on ~w, branch-free
-// (the chunks are checked on every frame, so the test is a few ALU operations per word and one
-// comparison per wave, not a chain of branches).
-__device__ __forceinline__ unsigned sentinel_bits(unsigned w) { return (~w - 0x00010001u) & w & 0x80008000u; }
-__device__ __forceinline__ unsigned sentinel_bits(const uint4& v) {
-    return sentinel_bits(v.x) | sentinel_bits(v.y) | sentinel_bits(v.z) | sentinel_bits(v.w);
+// The chunks are checked on every frame, so the test is branch-free and one operation per word:
+// 0xFFFF is the largest 16-bit value, so a packed unsigned maximum over all words has a 0xFFFF half
+// iff some word has one; the zero-halfword test on the complement of that maximum decides.
+typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned max_halves(unsigned x, unsigned y) {
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, x), __builtin_bit_cast(u16x2_t, y)));
 }
+__device__ __forceinline__ unsigned max_halves(const uint4& v) { return max_halves(max_halves(v.x, v.y), max_halves(v.z, v.w)); }
+__device__ __forceinline__ bool has_sentinel_half(unsigned w) { return ((~w - 0x00010001u) & w & 0x80008000u) != 0; }
 
 // Bounded wait of one wave.  `probe` points, for the lanes with probing set, at one element of each
 // producer's block: a cheap first look before the full loads.  Returns true if the wait was
@@ -103,17 +113,18 @@ __device__ __forceinline__ bool wait_probe(const bf16_t* probe, bool probing, un
     }
 }
 
+constexpr int XPAIR = 2 * 32 * 8;                      // elements of one pair of 8-column chunks over 32 rows (1 KB)
 template <int NQ>
 __device__ __forceinline__ void load_chunks(uint4 (&frag)[NQ], const bf16_t* p, bool valid) {
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) frag[q] = valid ? ld_coh_16B(p + q * 16) : make_uint4(0, 0, 0, 0);
+    for (int q = 0; q < NQ; ++q) frag[q] = valid ? ld_coh_16B(p + q * XPAIR) : make_uint4(0, 0, 0, 0);
 }
 template <int NQ>
 __device__ __forceinline__ bool all_written(const uint4 (&frag)[NQ]) {
     unsigned m = 0;
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) m |= sentinel_bits(frag[q]);
-    return __all(m == 0);
+    for (int q = 0; q < NQ; ++q) m = max_halves(m, max_halves(frag[q]));
+    return __all(!has_sentinel_half(m));
 }
 // The chunks in frag were loaded once; reloads them until no element of any lane is the sentinel
 // (or the wait is abandoned).  Normally the first check passes.
@@ -170,8 +181,10 @@ __device__ __forceinline__ GroupMap map_block(int NU, int nbg) {
 template <int NQ>
 __device__ __forceinline__ void load_chunks_cached(uint4 (&frag)[NQ], const bf16_t* p, bool valid) {
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) frag[q] = valid ? *reinterpret_cast<const uint4*>(p + q * 16) : make_uint4(0, 0, 0, 0);
+    for (int q = 0; q < NQ; ++q) frag[q] = valid ? *reinterpret_cast<const uint4*>(p + q * XPAIR) : make_uint4(0, 0, 0, 0);
 }
+// Element offset of column c (within a direction), row r of a tile, in the exchange order.
+__device__ __forceinline__ unsigned xoff(int c, int r) { return (unsigned)((c >> 3) * 256 + r * 8 + (c & 7)); }
 
 // Number of 32-row batch tiles of this workgroup's group that lie inside the batch.
 __device__ __forceinline__ int tiles_in_batch(int bg, int tiles_per_group, int B) {
@@ -184,7 +197,9 @@ __device__ __forceinline__ int tiles_in_batch(int bg, int tiles_per_group, int B
 // ------------------------------------------------------------------------------ forward
 // KW = contraction elements per wavefront: H = NW * KW.
 // FULL: B is a multiple of 32, so every row of every tile exists and no access is predicated.
-template <int NW, int KW, bool SENTINEL, bool FULL>
+// MULTI: a workgroup owns several batch tiles (tiles_per_group > 1); only then is there a next item
+// whose exchanged chunks can be loaded ahead, and only then are registers set aside for them.
+template <int NW, int KW, bool SENTINEL, bool FULL, bool MULTI>
 __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     constexpr int EPT = 16 / NW;                         // accumulator registers (batch rows) per thread
     constexpr int KSTEPS = KW / 16;                      // MFMA steps per gate per wavefront
@@ -220,7 +235,10 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     auto re = [](int e) { return 8 * (e >> 2) + (e & 3); };
     const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // into [.][2H] tensors (h, c)
     const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // into [.][8H] tensors (a_x, gates)
-    const unsigned ohp = (unsigned)(l32 * 2 * H + d * H + wave * KW + 8 * lh);   // A-fragment chunks of h: row l32
+    const int NT = (B + 31) / 32;                        // 32-row tiles of the batch
+    constexpr int XH = H / 16 * XPAIR;                   // exchange elements per (frame, direction, tile)
+    const unsigned ohp = (unsigned)(wave * (KW / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
+    const unsigned oxs = xoff(j, rb);                    // where this thread's h of row rb goes
 
     // Per-item inputs that do not depend on the exchange (a_x of the frame, previous cell state) are
     // loaded one item ahead, so that their HBM latency never sits on the frame-to-frame path.
@@ -247,7 +265,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     issue_inputs(0, ax, cp);
     // With several batch tiles per workgroup the next item's h was written a whole frame ago: its
     // chunks are loaded while this item computes (checked for the sentinel like any other load).
-    uint4 apre[KSTEPS];
+    uint4 apre[MULTI ? KSTEPS : 1];
     bool have_pre = false;
     for (int item = 0; item < nitems; ++item) {
         const int n = item / ntl, i = item - n * ntl;
@@ -264,18 +282,20 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             // previous h of this batch tile: row l32, 8 consecutive k per lane
             const int row = b0 + l32;
             const bool valid = FULL || row < B;
-            const bf16_t* hb = a.y + ((size_t)tp * B + b0) * 2 * H;       // uniform: previous frame, this tile
-            const bf16_t* hp = hb + (valid ? ohp : ohp - (unsigned)(l32 * 2 * H));
+            const bf16_t* hb = a.hx + ((size_t)(tp * 2 + d) * NT + (b0 >> 5)) * XH;   // uniform: previous frame, this tile
+            const bf16_t* hp = hb + ohp;
             uint4 afrag[KSTEPS];
             if (SENTINEL) {
                 // one probe per producing workgroup of this wavefront's k-range: its last unit, last valid row
                 const int prow = FULL ? b0 + 31 : min(b0 + 31, B - 1);
-                const bf16_t* probe = hb + (unsigned)((prow - b0) * 2 * H + d * H + wave * KW + (lane & (KW / 32 - 1)) * 32 + 31);
+                const bf16_t* probe = hb + xoff(wave * KW + (lane & (KW / 32 - 1)) * 32 + 31, prow - b0);
                 bool got = false, gu = false;
-                if (have_pre) {
+                if constexpr (MULTI) {
+                    if (have_pre) {
 #pragma unroll
-                    for (int q = 0; q < KSTEPS; ++q) afrag[q] = apre[q];
-                    got = all_written<KSTEPS>(afrag);
+                        for (int q = 0; q < KSTEPS; ++q) afrag[q] = apre[q];
+                        got = all_written<KSTEPS>(afrag);
+                    }
                 }
                 if (!got) {
                     gu = wait_probe(probe, lane < KW / 32, a.abort_word, a.limit_ticks);
@@ -288,7 +308,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                 wait_counter(cnt + i, (unsigned)(NU * n), a.abort_word, a.limit_ticks);
 #pragma unroll
                 for (int q = 0; q < KSTEPS; ++q)
-                    afrag[q] = valid ? *reinterpret_cast<const uint4*>(hp + q * 16) : make_uint4(0, 0, 0, 0);
+                    afrag[q] = valid ? *reinterpret_cast<const uint4*>(hp + q * XPAIR) : make_uint4(0, 0, 0, 0);
                 if (item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
             }
             f32x16_t acc[4];
@@ -301,13 +321,13 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) acc[g] = mfma_bf16(afrag[q], bfrag[g][q], acc[g]);
             have_pre = false;
-            if (SENTINEL && KW == 128 && ntl >= 2 && item + 1 < nitems) {
+            if constexpr (MULTI && SENTINEL && KW == 128) if (ntl >= 2 && item + 1 < nitems) {
                 const int n2 = (item + 1) / ntl, i2 = (item + 1) - n2 * ntl;
                 const int tp2 = d ? T - n2 : n2 - 1;
                 const int b02 = (gm.bg * a.tiles_per_group + i2) * 32;
                 const bool valid2 = FULL || b02 + l32 < B;
-                const bf16_t* hb2 = a.y + ((size_t)tp2 * B + b02) * 2 * H;
-                load_chunks_cached<KSTEPS>(apre, hb2 + (valid2 ? ohp : ohp - (unsigned)(l32 * 2 * H)), valid2);
+                const bf16_t* hb2 = a.hx + ((size_t)(tp2 * 2 + d) * NT + (b02 >> 5)) * XH;
+                load_chunks_cached<KSTEPS>(apre, hb2 + ohp, valid2);
                 have_pre = true;
             }
             // partial accumulators -> LDS as [wave][gate][reg/4][lane][reg%4]
@@ -318,30 +338,31 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                     l4[((wave * 4 + g) * 4 + rq) * 64 + lane] =
                         make_float4(acc[g][4 * rq], acc[g][4 * rq + 1], acc[g][4 * rq + 2], acc[g][4 * rq + 3]);
             if (SENTINEL) lds_barrier(); else __syncthreads();
+            // all partial sums of this thread's rows are read before any is added: the reads then
+            // overlap instead of each waiting for its LDS round trip
+            static_assert(EPT % 4 == 0, "rows per thread come in groups of four accumulator registers");
+            float4 part[NW][4][EPT / 4];
 #pragma unroll
             for (int w2 = 0; w2 < NW; ++w2)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    if (EPT >= 4) {
+                for (int g = 0; g < 4; ++g)
 #pragma unroll
-                        for (int e4 = 0; e4 < EPT / 4; ++e4) {
-                            const float4 v = l4[((w2 * 4 + g) * 4 + (EPT / 4) * wave + e4) * 64 + lane];
-                            sum[4 * e4][g] += v.x; sum[4 * e4 + 1][g] += v.y; sum[4 * e4 + 2][g] += v.z; sum[4 * e4 + 3][g] += v.w;
-                        }
-                    } else {
+                    for (int e4 = 0; e4 < EPT / 4; ++e4) part[w2][g][e4] = l4[((w2 * 4 + g) * 4 + (EPT / 4) * wave + e4) * 64 + lane];
 #pragma unroll
-                        for (int e = 0; e < EPT; ++e) {
-                            const int r = EPT * wave + e;
-                            sum[e][g] += lds[((((w2 * 4 + g) * 4 + (r >> 2)) * 64 + lane) << 2) + (r & 3)];
-                        }
+            for (int w2 = 0; w2 < NW; ++w2)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e4 = 0; e4 < EPT / 4; ++e4) {
+                        const float4 v = part[w2][g][e4];
+                        sum[4 * e4][g] += v.x; sum[4 * e4 + 1][g] += v.y; sum[4 * e4 + 2][g] += v.z; sum[4 * e4 + 3][g] += v.w;
                     }
-                }
         } else if (item + 1 < nitems) {
             issue_inputs(item + 1, axn, cpn);
         }
         // cell arithmetic; h goes out first because it is all the other workgroups wait for
-        float gi[EPT], gf[EPT], gg[EPT], go[EPT], cn[EPT];
-        bf16_t* yb = a.y + ((size_t)t * B + b0) * 2 * H;
+        float gi[EPT], gf[EPT], gg[EPT], go[EPT], cn[EPT], hn[EPT];
+        bf16_t* hxb = a.hx + ((size_t)(t * 2 + d) * NT + (b0 >> 5)) * XH;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             gi[e] = fast_sigmoid(ax[e][0] + sum[e][0]);
@@ -349,21 +370,24 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             gg[e] = fast_tanh(ax[e][2] + sum[e][2]);
             go[e] = fast_sigmoid(ax[e][3] + sum[e][3]);
             cn[e] = gf[e] * cp[e] + gi[e] * gg[e];
-            const float h = go[e] * fast_tanh(cn[e]);
+            hn[e] = go[e] * fast_tanh(cn[e]);
             if (FULL || b0 + rb + re(e) < B) {
-                bf16_t* yp = yb + (o2b + (unsigned)(re(e) * 2 * H));
-                if (SENTINEL) st_coh_bf16(yp, h); else *yp = f2bf(h);
+                bf16_t* xp = hxb + (oxs + (unsigned)(re(e) * 8));
+                if (SENTINEL) st_coh_bf16(xp, hn[e]); else *xp = f2bf(hn[e]);
             }
         }
         if (SENTINEL) lds_barrier();                     // frees the LDS buffer for the next item
         else signal_counter(cnt + i);                    // barrier inside: same role
-        // saved for the backward pass only: off the critical path of the exchange
+        // row-major outputs (h for the next layer, c and the gates for the backward pass): off the
+        // critical path of the exchange
         float* cb = a.c + ((size_t)t * B + b0) * 2 * H;
+        bf16_t* yb = a.y + ((size_t)t * B + b0) * 2 * H;
         bf16_t* gb = a.gates + ((size_t)t * B + b0) * 8 * H;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             if (FULL || b0 + rb + re(e) < B) {
                 cb[o2b + (unsigned)(re(e) * 2 * H)] = cn[e];
+                yb[o2b + (unsigned)(re(e) * 2 * H)] = f2bf(hn[e]);
                 bf16_t* gp = gb + (o8b + (unsigned)(re(e) * 8 * H));
                 gp[0] = f2bf(gi[e]); gp[(unsigned)H] = f2bf(gf[e]); gp[(unsigned)(2 * H)] = f2bf(gg[e]); gp[(unsigned)(3 * H)] = f2bf(go[e]);
             }
@@ -379,7 +403,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------ backward
-template <int NW, int KW, bool SENTINEL, bool FULL>
+template <int NW, int KW, bool SENTINEL, bool FULL, bool MULTI>
 __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     constexpr int EPT = 16 / NW;
     constexpr int KSTEPS = 4 * KW / 16;                  // the contraction runs over the 4H gate rows
@@ -413,7 +437,10 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     const unsigned o1b = (unsigned)(rb * H + j);                 // into [.][H] (carried dE/dc),
     const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // [.][2H] (c, dy)
     const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // and [.][8H] tensors (gates, dE/da)
-    const unsigned oap = (unsigned)(l32 * 8 * H + d * 4 * H + wave * KWB + 8 * lh);   // A-fragment chunks of dE/da: row l32
+    const int NT = (B + 31) / 32;
+    constexpr int XA = 4 * H / 16 * XPAIR;               // exchange elements per (frame, direction, tile)
+    const unsigned oap = (unsigned)(wave * (KWB / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
+    const unsigned oxs = xoff(j, rb);                    // where this thread's dE/da of gate 0, row rb goes
 
     // Saved activations of an item, loaded one item ahead (raw bf16 for the gates and dy).
     struct Inputs { bf16_t g[EPT][4]; bf16_t dy[EPT]; float c[EPT], cp[EPT], dcr[EPT]; };
@@ -446,7 +473,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     const int nitems = T * ntl;
     Inputs cur;
     issue_inputs(0, cur);
-    uint4 apre[8];                                       // first slab of the next item, loaded ahead (several tiles only)
+    uint4 apre[MULTI ? 8 : 1];                           // first slab of the next item, loaded ahead (several tiles only)
     bool have_pre = false;
     for (int item = 0; item < nitems; ++item) {
         const int ni = item / ntl, i = item - ni * ntl;
@@ -461,8 +488,8 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         if (n < T - 1) {
             const int row = b0 + l32;
             const bool valid = FULL || row < B;
-            const bf16_t* ab = a.da + ((size_t)tn * B + b0) * 8 * H;      // uniform: the frame visited before, this tile
-            const bf16_t* ap = ab + (valid ? oap : oap - (unsigned)(l32 * 8 * H));
+            const bf16_t* ab = a.dax + ((size_t)(tn * 2 + d) * NT + (b0 >> 5)) * XA;   // uniform: the frame visited before, this tile
+            const bf16_t* ap = ab + oap;
             f32x16_t acc;
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
@@ -470,13 +497,15 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 // the gate rows of this wavefront come from KWB/32 producers: probe each one's last unit,
                 // then stream the slabs of 128 gate rows with the next slab's loads in flight
                 const int prow = FULL ? b0 + 31 : min(b0 + 31, B - 1);
-                const bf16_t* probe = ab + (unsigned)((prow - b0) * 8 * H + d * 4 * H + wave * KWB + (lane & (4 * KW / 32 - 1)) * 32 + 31);
+                const bf16_t* probe = ab + xoff(wave * KWB + (lane & (4 * KW / 32 - 1)) * 32 + 31, prow - b0);
                 uint4 afrag[2][8];
                 bool got = false, gu = false;
-                if (have_pre) {
+                if constexpr (MULTI) {
+                    if (have_pre) {
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) afrag[0][q] = apre[q];
-                    got = all_written<8>(afrag[0]);
+                        for (int q = 0; q < 8; ++q) afrag[0][q] = apre[q];
+                        got = all_written<8>(afrag[0]);
+                    }
                 }
                 if (!got) {
                     gu = wait_probe(probe, lane < 4 * KW / 32, a.abort_word, a.limit_ticks);
@@ -485,24 +514,24 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 }
 #pragma unroll
                 for (int sl = 0; sl < KSTEPS / 8; ++sl) {
-                    if (sl + 1 < KSTEPS / 8) load_chunks_cached<8>(afrag[(sl + 1) & 1], ap + (sl + 1) * 128, valid);
+                    if (sl + 1 < KSTEPS / 8) load_chunks_cached<8>(afrag[(sl + 1) & 1], ap + (sl + 1) * 8 * XPAIR, valid);
                     else {
                         if (item + 1 < nitems) issue_inputs(item + 1, nxt);
                         have_pre = false;
-                        if (KW == 128 && ntl >= 2 && item + 1 < nitems) {
+                        if constexpr (MULTI && KW == 128) if (ntl >= 2 && item + 1 < nitems) {
                             const int ni2 = (item + 1) / ntl, i2 = (item + 1) - ni2 * ntl;
                             const int n2 = T - 1 - ni2;
                             if (n2 < T - 1) {
                                 const int tn2 = d ? T - 2 - n2 : n2 + 1;
                                 const int b02 = (gm.bg * a.tiles_per_group + i2) * 32;
                                 const bool valid2 = FULL || b02 + l32 < B;
-                                const bf16_t* ab2 = a.da + ((size_t)tn2 * B + b02) * 8 * H;
-                                load_chunks_cached<8>(apre, ab2 + (valid2 ? oap : oap - (unsigned)(l32 * 8 * H)), valid2);
+                                const bf16_t* ab2 = a.dax + ((size_t)(tn2 * 2 + d) * NT + (b02 >> 5)) * XA;
+                                load_chunks_cached<8>(apre, ab2 + oap, valid2);
                                 have_pre = true;
                             }
                         }
                     }
-                    gu = ensure_written<8>(afrag[sl & 1], ap + sl * 128, valid, gu, a.abort_word, a.limit_ticks);
+                    gu = ensure_written<8>(afrag[sl & 1], ap + sl * 8 * XPAIR, valid, gu, a.abort_word, a.limit_ticks);
 #pragma unroll
                     for (int q = 0; q < 8; ++q) acc = mfma_bf16(afrag[sl & 1][q], bfrag[sl * 8 + q], acc);
                 }
@@ -513,7 +542,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                     uint4 afrag[8];
 #pragma unroll
                     for (int q = 0; q < 8; ++q)
-                        afrag[q] = valid ? *reinterpret_cast<const uint4*>(ap + (q0 + q) * 16) : make_uint4(0, 0, 0, 0);
+                        afrag[q] = valid ? *reinterpret_cast<const uint4*>(ap + (q0 + q) * XPAIR) : make_uint4(0, 0, 0, 0);
                     if (q0 + 8 >= KSTEPS && item + 1 < nitems) issue_inputs(item + 1, nxt);
 #pragma unroll
                     for (int q = 0; q < 8; ++q) acc = mfma_bf16(afrag[q], bfrag[q0 + q], acc);
@@ -523,18 +552,27 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
             for (int rq = 0; rq < 4; ++rq)
                 l4[(wave * 4 + rq) * 64 + lane] = make_float4(acc[4 * rq], acc[4 * rq + 1], acc[4 * rq + 2], acc[4 * rq + 3]);
             if (SENTINEL) lds_barrier(); else __syncthreads();
+            // this thread's rows are EPT/4 whole float4 of each wavefront's partial tile; all are read
+            // before any is added so that the LDS round trips overlap
+            static_assert(EPT % 4 == 0, "rows per thread come in groups of four accumulator registers");
+            float4 part[NW][EPT / 4];
 #pragma unroll
             for (int w2 = 0; w2 < NW; ++w2)
 #pragma unroll
-                for (int e = 0; e < EPT; ++e) {
-                    const int r = EPT * wave + e;
-                    dh[e] += lds[(((w2 * 4 + (r >> 2)) * 64 + lane) << 2) + (r & 3)];
+                for (int e4 = 0; e4 < EPT / 4; ++e4) part[w2][e4] = l4[(w2 * 4 + (EPT / 4) * wave + e4) * 64 + lane];
+#pragma unroll
+            for (int w2 = 0; w2 < NW; ++w2)
+#pragma unroll
+                for (int e4 = 0; e4 < EPT / 4; ++e4) {
+                    const float4 v = part[w2][e4];
+                    dh[4 * e4] += v.x; dh[4 * e4 + 1] += v.y; dh[4 * e4 + 2] += v.z; dh[4 * e4 + 3] += v.w;
                 }
         } else if (item + 1 < nitems) {
             issue_inputs(item + 1, nxt);
         }
         float dcf[EPT];
-        bf16_t* dab = a.da + ((size_t)t * B + b0) * 8 * H;
+        unsigned dav[EPT][2];                             // (i, f) and (g, o) as bf16 pairs: kept for the row-major copy below
+        bf16_t* dxb = a.dax + ((size_t)(t * 2 + d) * NT + (b0 >> 5)) * XA;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             const float gi = bf2f(cur.g[e][0]), gf = bf2f(cur.g[e][1]), gg = bf2f(cur.g[e][2]), go = bf2f(cur.g[e][3]);
@@ -546,22 +584,30 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
             const float da_f = dc * cur.cp[e] * gf * (1.0f - gf);
             const float da_g = dc * gi * (1.0f - gg * gg);
             dcf[e] = dc * gf;
+            dav[e][0] = (unsigned)coh_bf16(da_i) | ((unsigned)coh_bf16(da_f) << 16);
+            dav[e][1] = (unsigned)coh_bf16(da_g) | ((unsigned)coh_bf16(da_o) << 16);
             if (FULL || b0 + rb + re(e) < B) {
-                bf16_t* dp = dab + (o8b + (unsigned)(re(e) * 8 * H));
-                if (SENTINEL) {
-                    st_coh_bf16(dp, da_i); st_coh_bf16(dp + (unsigned)H, da_f);
-                    st_coh_bf16(dp + (unsigned)(2 * H), da_g); st_coh_bf16(dp + (unsigned)(3 * H), da_o);
-                } else {
-                    dp[0] = f2bf(da_i); dp[(unsigned)H] = f2bf(da_f); dp[(unsigned)(2 * H)] = f2bf(da_g); dp[(unsigned)(3 * H)] = f2bf(da_o);
+                bf16_t* xp = dxb + (oxs + (unsigned)(re(e) * 8));       // gate g: H columns = H/16 chunk pairs further
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const bf16_t v = (bf16_t)(dav[e][g >> 1] >> (16 * (g & 1)));
+                    if (SENTINEL) __hip_atomic_store(xp + (unsigned)(g * (H / 16) * XPAIR), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    else xp[(unsigned)(g * (H / 16) * XPAIR)] = v;
                 }
             }
         }
         if (SENTINEL) lds_barrier();
         else signal_counter(cnt + i);
+        // row-major dE/da for the weight- and input-gradient products, and the carried dE/dc
         float* dcb = a.dc + ((size_t)d * B + b0) * H;
+        bf16_t* dab = a.da + ((size_t)t * B + b0) * 8 * H;
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
-            if (FULL || b0 + rb + re(e) < B) dcb[o1b + (unsigned)(re(e) * H)] = dcf[e];
+            if (FULL || b0 + rb + re(e) < B) {
+                dcb[o1b + (unsigned)(re(e) * H)] = dcf[e];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) dab[o8b + (unsigned)((re(e) * 8 + g) * H)] = (bf16_t)(dav[e][g >> 1] >> (16 * (g & 1)));
+            }
         // next item's inputs; with one tile per workgroup its carried dE/dc is the one just computed
         cur = nxt;
         if (ntl == 1) {
@@ -613,29 +659,37 @@ hipError_t prepare(K kernel, int threads, size_t dyn_lds, int grid, bool* fits) 
     return hipSuccess;
 }
 
-template <int NW, int KW, bool S, bool FULL>
-hipError_t run_fwd_as(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
+template <int NW, int KW, bool S, bool FULL, bool MULTI>
+hipError_t run_fwd_m(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
     const size_t lds = (size_t)NW * 4 * 4 * 64 * 16;
     bool fits = false;
-    hipError_t e = prepare(rec_fwd_kernel<NW, KW, S, FULL>, 64 * NW, lds, grid, &fits);
+    hipError_t e = prepare(rec_fwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &fits);
     if (e != hipSuccess || !fits) return e;
-    hipLaunchKernelGGL((rec_fwd_kernel<NW, KW, S, FULL>), dim3(grid), dim3(64 * NW), lds, st, a);
+    hipLaunchKernelGGL((rec_fwd_kernel<NW, KW, S, FULL, MULTI>), dim3(grid), dim3(64 * NW), lds, st, a);
     *launched = true;
     return hipGetLastError();
+}
+template <int NW, int KW, bool S, bool FULL>
+hipError_t run_fwd_as(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
+    return a.tiles_per_group > 1 ? run_fwd_m<NW, KW, S, FULL, true>(a, grid, st, launched) : run_fwd_m<NW, KW, S, FULL, false>(a, grid, st, launched);
 }
 template <int NW, int KW, bool S>
 hipError_t run_fwd(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
     return a.B % 32 == 0 ? run_fwd_as<NW, KW, S, true>(a, grid, st, launched) : run_fwd_as<NW, KW, S, false>(a, grid, st, launched);
 }
-template <int NW, int KW, bool S, bool FULL>
-hipError_t run_bwd_as(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
+template <int NW, int KW, bool S, bool FULL, bool MULTI>
+hipError_t run_bwd_m(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
     const size_t lds = (size_t)NW * 4 * 64 * 16;
     bool fits = false;
-    hipError_t e = prepare(rec_bwd_kernel<NW, KW, S, FULL>, 64 * NW, lds, grid, &fits);
+    hipError_t e = prepare(rec_bwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &fits);
     if (e != hipSuccess || !fits) return e;
-    hipLaunchKernelGGL((rec_bwd_kernel<NW, KW, S, FULL>), dim3(grid), dim3(64 * NW), lds, st, a);
+    hipLaunchKernelGGL((rec_bwd_kernel<NW, KW, S, FULL, MULTI>), dim3(grid), dim3(64 * NW), lds, st, a);
     *launched = true;
     return hipGetLastError();
+}
+template <int NW, int KW, bool S, bool FULL>
+hipError_t run_bwd_as(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
+    return a.tiles_per_group > 1 ? run_bwd_m<NW, KW, S, FULL, true>(a, grid, st, launched) : run_bwd_m<NW, KW, S, FULL, false>(a, grid, st, launched);
 }
 template <int NW, int KW, bool S>
 hipError_t run_bwd(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
@@ -644,13 +698,12 @@ hipError_t run_bwd(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched
 
 }  // namespace
 
-// Supported widths: H = 128 (two wavefronts with 64 contraction elements each), 256 and 512 (two and
-// four wavefronts with 128 each) and 1024 (four wavefronts with 256 each: the U_h slice then fills 256
-// registers per lane, which leaves no room for the predicates of a ragged batch, so that width
-// needs B to be a multiple of 32).  Returns the wavefronts per workgroup, 0 if unsupported.
+// Supported widths: H = 128, 256, 512 and 1024, always on four wavefronts that split the contraction
+// (32, 64, 128, 256 elements each: four batch rows per thread in every variant).  At H = 1024 the U_h
+// slice fills 256 registers per lane, which leaves no room for the predicates of a ragged batch, so
+// that width needs B to be a multiple of 32.  Returns the wavefronts per workgroup, 0 if unsupported.
 int rec_waves_for(int H, int B) {
-    if (H == 128 || H == 256) return 2;
-    if (H == 512) return 4;
+    if (H == 128 || H == 256 || H == 512) return 4;
     if (H == 1024 && B % 32 == 0) return 4;
     return 0;
 }
@@ -680,8 +733,8 @@ hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bo
     *launched = false;
     const int grid = 2 * a.nbg * (a.H / 32);
     switch (a.H) {
-        case 128: return sentinel ? run_fwd<2, 64, true>(a, grid, st, launched) : run_fwd<2, 64, false>(a, grid, st, launched);
-        case 256: return sentinel ? run_fwd<2, 128, true>(a, grid, st, launched) : run_fwd<2, 128, false>(a, grid, st, launched);
+        case 128: return sentinel ? run_fwd<4, 32, true>(a, grid, st, launched) : run_fwd<4, 32, false>(a, grid, st, launched);
+        case 256: return sentinel ? run_fwd<4, 64, true>(a, grid, st, launched) : run_fwd<4, 64, false>(a, grid, st, launched);
         case 512: return sentinel ? run_fwd<4, 128, true>(a, grid, st, launched) : run_fwd<4, 128, false>(a, grid, st, launched);
         case 1024:
             if (a.B % 32 != 0) return hipSuccess;
@@ -694,8 +747,8 @@ hipError_t launch_rec_bwd(const RecBwdArgs& a, bool sentinel, hipStream_t st, bo
     *launched = false;
     const int grid = 2 * a.nbg * (a.H / 32);
     switch (a.H) {
-        case 128: return sentinel ? run_bwd<2, 64, true>(a, grid, st, launched) : run_bwd<2, 64, false>(a, grid, st, launched);
-        case 256: return sentinel ? run_bwd<2, 128, true>(a, grid, st, launched) : run_bwd<2, 128, false>(a, grid, st, launched);
+        case 128: return sentinel ? run_bwd<4, 32, true>(a, grid, st, launched) : run_bwd<4, 32, false>(a, grid, st, launched);
+        case 256: return sentinel ? run_bwd<4, 64, true>(a, grid, st, launched) : run_bwd<4, 64, false>(a, grid, st, launched);
         case 512: return sentinel ? run_bwd<4, 128, true>(a, grid, st, launched) : run_bwd<4, 128, false>(a, grid, st, launched);
         case 1024:
             if (a.B % 32 != 0) return hipSuccess;
