@@ -219,7 +219,34 @@ def main():
                              "bytes_per_launch": bytes_per,
                              "traffic": (MEASURED_MIX_BYTES_PER_PAIR[w.name] * R / 2
                                          if w.name in MEASURED_MIX_BYTES_PER_PAIR and B == w.dims()["B"] else None)}
+        # the same replicas through the R-way average of the synchronous strategy (Fig. 3a)
+        for it in range(2):
+            bl.sync_average(reps, shs, lrn.n, R)
+        ev[0].record()
+        for it in range(nmix):
+            bl.sync_average(reps, shs, lrn.n, R)
+        ev[1].record()
+        torch.cuda.synchronize()
+        sync_ms = ev[0].elapsed_time(ev[1]) / nmix
+        out["sync_average"] = {"replicas": R, "ms": sync_ms, "bound": "hbm", "achieved": bytes_per / (sync_ms * 1e-3) / 1e9,
+                               "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": bytes_per / (sync_ms * 1e-3) / PEAK_HBM,
+                               "bytes_per_launch": bytes_per}
         del reps, shs
+    # Eq. 4 for the learner and its neighbour in one pass (update of both + average), against the two-call form
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    nb_grad = lrn.grad.clone()
+    for it in range(3):
+        bl.sgd_mix_pair(lrn.theta, nb_theta, lrn.shadow, nb_shadow, lrn.grad, nb_grad, lrn.n, 0.0)
+    ev[0].record()
+    for it in range(20):
+        bl.sgd_mix_pair(lrn.theta, nb_theta, lrn.shadow, nb_shadow, lrn.grad, nb_grad, lrn.n, 0.0)
+    ev[1].record()
+    torch.cuda.synchronize()
+    pair_ms = ev[0].elapsed_time(ev[1]) / 20
+    pair_bytes = 2 * lrn.n * (12 + (2 if bf else 0))
+    out["sgd_mix_pair"] = {"ms": pair_ms, "bound": "hbm", "achieved": pair_bytes / (pair_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9,
+                           "unit": "GB/s", "frac": pair_bytes / (pair_ms * 1e-3) / PEAK_HBM, "bytes_per_launch": pair_bytes,
+                           "note": "one pass for both replicas' sgd_step and their adpsgd_mix (lr = 0 here so the weights stay put)"}
 
     # ---- the oracle on this machine's host cores, on a bounded sample of the same workload ------
     if not args.no_cpu_baseline:

@@ -107,6 +107,26 @@ int sgd_step(float* theta_master, void* theta_bf16_or_null, const float* grad, s
 int adpsgd_mix(float* const* theta_master, void* const* theta_bf16_or_null, size_t n, int R,
                const int32_t* partner, void* stream);
 
+/* Eq. 1c and Eq. 4 (second line) for one pair in a single pass: theta_i' = theta_i - lr grad_i and
+   theta_j' = theta_j - lr grad_j (momentum as in sgd_step, each replica with its own velocity), then both
+   replicas become (theta_i' + theta_j')/2.  Same arithmetic, element by element, as sgd_step on each
+   replica followed by adpsgd_mix on the pair; the weights are read and written once instead of twice.
+   All pointers are device pointers, 16-byte aligned, n elements; the bf16 copies are both given or both NULL. */
+int sgd_mix_pair(float* theta_i, float* theta_j, void* theta_bf16_i_or_null, void* theta_bf16_j_or_null,
+                 const float* grad_i, const float* grad_j, size_t n, float lr, float momentum,
+                 float* velocity_i_or_null, float* velocity_j_or_null, void* stream);
+
+/* The synchronous strategy of section 3.2 (Fig. 3a: W = allreduce(W') / lambda) for R replicas held in one
+   GPU's memory: every replica becomes the mean of all R, summed in the order 0..R-1 in float and scaled
+   by 1/R.  theta_master / theta_bf16_or_null: HOST arrays of R device pointers as for adpsgd_mix. */
+int sync_average(float* const* theta_master, void* const* theta_bf16_or_null, size_t n, int R, void* stream);
+
+/* Learning rate of a 1-based epoch under section 3.1's recipe (host arithmetic, no device work): linear
+   warm-up from base_lr to peak_lr over the first warmup_epochs epochs, then a factor 1/sqrt(2) per epoch
+   from epoch anneal_from on.  The paper's runs: warmup_epochs = 10, anneal_from = 11, 16 epochs;
+   base_lr == peak_lr gives the batch-256 recipe without warm-up. */
+double blstm_lr_schedule(int epoch, double base_lr, double peak_lr, int warmup_epochs, int anneal_from);
+
 /* The alternating ring matching of section 3.2 (0-based): learners 0,2,4,.. are the senders; on even
    steps sender i pairs with i+1, on odd steps with (i-1) mod R.  R must be even and >= 2. */
 int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);

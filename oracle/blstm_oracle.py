@@ -316,3 +316,28 @@ def lr_schedule(epoch: int, base_lr: float, peak_lr: float, warmup_epochs: int =
         return base_lr + (peak_lr - base_lr) * (epoch - 1) / (warmup_epochs - 1)
     k = max(0, epoch - anneal_from + 1)
     return peak_lr * (2.0 ** (-0.5 * k))
+
+
+def sgd_mix_pair(theta_i, theta_j, grad_i, grad_j, lr, momentum=0.0, velocity_i=None, velocity_j=None):
+    """Both lines of Eq. 4 for one pair: each replica takes its own step of Eq. 1c, then both become
+    the average of the two results.  Returns (theta_new, velocity_i_new, velocity_j_new); theta_new is
+    the common value of both replicas."""
+    ti, vi = sgd_step(theta_i, grad_i, lr, momentum, velocity_i)
+    tj, vj = sgd_step(theta_j, grad_j, lr, momentum, velocity_j)
+    return (ti + tj) / 2.0, vi, vj
+
+
+def sync_average(thetas):
+    """SYNC of section 3.2 (Fig. 3a): W = allreduce(W') / lambda: every learner ends with the mean of
+    all learners' updated weights."""
+    m = np.mean(np.stack([np.asarray(t, dtype=np.float64) for t in thetas]), axis=0)
+    return [m.copy() for _ in thetas]
+
+
+def stale_adpsgd_step(thetas, grads, partner, lr):
+    """One iteration in the integration order of Fig. 3b: g = calGrad(W) on the learner's own weights,
+    W = pull_weights() (the average of what the pair pushed at the end of the previous iteration, which
+    is what each learner now holds), W' = apply(W, g), push_weights(W').  grads[i] must have been
+    computed on thetas[i]; the gradient is therefore one averaging step stale when it is applied."""
+    pulled = adpsgd_mix(thetas, partner)
+    return [sgd_step(pulled[i], grads[i], lr)[0] for i in range(len(thetas))]

@@ -20,6 +20,7 @@ BLSTM_MAX_REPLICAS = 64
 EXPORTS = [
     "blstm_create", "blstm_destroy", "blstm_param_count", "blstm_workspace_bytes", "blstm_param_offset",
     "blstm_bind", "blstm_forward", "softmax_xent_fwd_bwd", "blstm_backward", "sgd_step", "adpsgd_mix",
+    "sgd_mix_pair", "sync_average", "blstm_lr_schedule",
     "adpsgd_ring_partner", "blstm_shadow_refresh", "blstm_set_option", "blstm_device_status", "blstm_profile_enable", "blstm_profile_read",
     "blstm_profile_classes", "blstm_profile_name", "blstm_last_error",
 ]
@@ -69,6 +70,13 @@ def lib():
     L.sgd_step.restype = c_int
     L.adpsgd_mix.argtypes = [POINTER(c_void_p), POINTER(c_void_p), c_size_t, c_int, POINTER(c_int32), c_void_p]
     L.adpsgd_mix.restype = c_int
+    L.sgd_mix_pair.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_float, c_float,
+                               c_void_p, c_void_p, c_void_p]
+    L.sgd_mix_pair.restype = c_int
+    L.sync_average.argtypes = [POINTER(c_void_p), POINTER(c_void_p), c_size_t, c_int, c_void_p]
+    L.sync_average.restype = c_int
+    L.blstm_lr_schedule.argtypes = [c_int, c_double, c_double, c_int, c_int]
+    L.blstm_lr_schedule.restype = c_double
     L.adpsgd_ring_partner.argtypes = [c_int, c_int64, POINTER(c_int32)]
     L.adpsgd_ring_partner.restype = c_int
     L.blstm_shadow_refresh.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
@@ -176,6 +184,25 @@ def adpsgd_mix(theta_master, theta_bf16_or_null, n, R, partner, stream=None):
         shadows = (c_void_p * R)(*[_ptr(t) for t in theta_bf16_or_null])
     part = (c_int32 * R)(*[int(p) for p in partner])
     return _check(lib().adpsgd_mix(masters, shadows, n, R, part, _stream(stream)))
+
+
+def sgd_mix_pair(theta_i, theta_j, theta_bf16_i_or_null, theta_bf16_j_or_null, grad_i, grad_j, n, lr, momentum=0.0,
+                 velocity_i_or_null=None, velocity_j_or_null=None, stream=None):
+    return _check(lib().sgd_mix_pair(_ptr(theta_i), _ptr(theta_j), _ptr(theta_bf16_i_or_null), _ptr(theta_bf16_j_or_null),
+                                     _ptr(grad_i), _ptr(grad_j), n, lr, momentum, _ptr(velocity_i_or_null),
+                                     _ptr(velocity_j_or_null), _stream(stream)))
+
+
+def sync_average(theta_master, theta_bf16_or_null, n, R, stream=None):
+    masters = (c_void_p * R)(*[_ptr(t) for t in theta_master])
+    shadows = None
+    if theta_bf16_or_null is not None:
+        shadows = (c_void_p * R)(*[_ptr(t) for t in theta_bf16_or_null])
+    return _check(lib().sync_average(masters, shadows, n, R, _stream(stream)))
+
+
+def blstm_lr_schedule(epoch, base_lr, peak_lr, warmup_epochs=10, anneal_from=11):
+    return float(lib().blstm_lr_schedule(int(epoch), float(base_lr), float(peak_lr), int(warmup_epochs), int(anneal_from)))
 
 
 def adpsgd_ring_partner(R, step):

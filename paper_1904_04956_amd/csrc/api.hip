@@ -638,6 +638,50 @@ int adpsgd_mix(float* const* theta, void* const* shadow, size_t n, int R, const 
     return check_hip(launch_mix(p, n, static_cast<hipStream_t>(stream)), "adpsgd_mix");
 }
 
+int sgd_mix_pair(float* theta_i, float* theta_j, void* shadow_i, void* shadow_j, const float* grad_i, const float* grad_j,
+                 size_t n, float lr, float momentum, float* velocity_i, float* velocity_j, void* stream) {
+    if (!theta_i || !theta_j || !grad_i || !grad_j) return fail(BLSTM_ERR_NULL, "sgd_mix_pair: null argument");
+    if ((shadow_i == nullptr) != (shadow_j == nullptr)) return fail(BLSTM_ERR_NULL, "sgd_mix_pair: give both bf16 copies or neither");
+    if (momentum != 0.0f && (!velocity_i || !velocity_j)) return fail(BLSTM_ERR_NULL, "sgd_mix_pair: momentum needs both velocity buffers");
+    if (theta_i == theta_j) return fail(BLSTM_ERR_DIM, "sgd_mix_pair: the two replicas share a buffer");
+    if (!aligned16(theta_i) || !aligned16(theta_j) || !aligned16(grad_i) || !aligned16(grad_j) ||
+        (shadow_i && (!aligned16(shadow_i) || !aligned16(shadow_j))) ||
+        (momentum != 0.0f && (!aligned16(velocity_i) || !aligned16(velocity_j))))
+        return fail(BLSTM_ERR_ALIGN, "sgd_mix_pair: pointers must be 16-byte aligned");
+    return check_hip(launch_sgd_mix_pair(theta_i, theta_j, grad_i, grad_j, velocity_i, velocity_j,
+                                         static_cast<unsigned short*>(shadow_i), static_cast<unsigned short*>(shadow_j),
+                                         n, lr, momentum, static_cast<hipStream_t>(stream)), "sgd_mix_pair");
+}
+
+int sync_average(float* const* theta, void* const* shadow, size_t n, int R, void* stream) {
+    if (!theta) return fail(BLSTM_ERR_NULL, "sync_average: null argument");
+    if (R < 1 || R > BLSTM_MAX_REPLICAS) return fail(BLSTM_ERR_DIM, "sync_average: R must be in 1..%d", BLSTM_MAX_REPLICAS);
+    static_assert(BLSTM_MAX_REPLICAS == BLSTM_MAX_REPLICA_PTRS, "the kernel's pointer table must hold every replica");
+    ReplicaSet p{};
+    p.R = R;
+    for (int i = 0; i < R; ++i) {
+        if (!theta[i] || (shadow && !shadow[i])) return fail(BLSTM_ERR_NULL, "sync_average: null replica pointer %d", i);
+        if (!aligned16(theta[i]) || (shadow && !aligned16(shadow[i]))) return fail(BLSTM_ERR_ALIGN, "sync_average: replica %d is not 16-byte aligned", i);
+        for (int k = 0; k < i; ++k)
+            if (theta[k] == theta[i]) return fail(BLSTM_ERR_DIM, "sync_average: replicas %d and %d share a buffer", k, i);
+        p.t[i] = theta[i];
+        p.s[i] = shadow ? static_cast<unsigned short*>(shadow[i]) : nullptr;
+    }
+    return check_hip(launch_sync_average(p, n, static_cast<hipStream_t>(stream)), "sync_average");
+}
+
+double blstm_lr_schedule(int epoch, double base_lr, double peak_lr, int warmup_epochs, int anneal_from) {
+    if (epoch <= warmup_epochs) {
+        if (warmup_epochs <= 1) return peak_lr;
+        return base_lr + (peak_lr - base_lr) * (double)(epoch - 1) / (double)(warmup_epochs - 1);
+    }
+    int k = epoch - anneal_from + 1;
+    if (k < 0) k = 0;
+    double lr = peak_lr;
+    for (int i = 0; i < k; ++i) lr *= 0.70710678118654752440;
+    return lr;
+}
+
 int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out) {
     if (!partner_out) return fail(BLSTM_ERR_NULL, "adpsgd_ring_partner: null argument");
     if (R < 2 || (R & 1) || step < 0) return fail(BLSTM_ERR_DIM, "adpsgd_ring_partner: R must be even and >= 2, step >= 0");

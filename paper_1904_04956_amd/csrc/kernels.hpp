@@ -8,6 +8,7 @@
 namespace blstm {
 
 constexpr int BLSTM_MAX_PAIRS = 32;                  // pairs of one matching (64 replicas)
+constexpr int BLSTM_MAX_REPLICA_PTRS = 64;           // replicas of one average (equals BLSTM_MAX_REPLICAS of the C header)
 
 // ---- LSTM cell, one visited frame of both directions ---------------------------------
 // Index d = direction.  Row strides are in elements.
@@ -96,5 +97,13 @@ struct MixPairs {
 };
 hipError_t launch_mix(const MixPairs& p, size_t n, hipStream_t st);
 hipError_t launch_shadow(const float* theta, unsigned short* shadow, size_t n, hipStream_t st);
+hipError_t launch_sgd_mix_pair(float* ti, float* tj, const float* gi, const float* gj, float* vi, float* vj,
+                               unsigned short* si, unsigned short* sj, size_t n, float lr, float mu, hipStream_t st);
+struct ReplicaSet {
+    float* t[BLSTM_MAX_REPLICA_PTRS];
+    unsigned short* s[BLSTM_MAX_REPLICA_PTRS];
+    int R;
+};
+hipError_t launch_sync_average(const ReplicaSet& p, size_t n, hipStream_t st);
 
 }  // namespace blstm

@@ -65,6 +65,10 @@ __global__ __launch_bounds__(256) void softmax_rows_bf16_regs_kernel(bf16_t* u, 
         }
     }
     mx = block_reduce(mx, true, sh);
+    // exp(x - mx) = exp2(x * log2(e) - mx * log2(e)): one multiply-add and the hardware exp2 per element
+    // (the argument is <= 0; a result below the normal range flushes to 0, as its probability does in bf16)
+    const float L2E = 1.44269504f;
+    const float mxl = mx * L2E;
     float sum = 0.0f;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
@@ -73,28 +77,32 @@ __global__ __launch_bounds__(256) void softmax_rows_bf16_regs_kernel(bf16_t* u, 
             const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                sum += __expf(bf2f((bf16_t)(w[q] & 0xFFFFu)) - mx) + __expf(bf2f((bf16_t)(w[q] >> 16)) - mx);
+                sum += __builtin_amdgcn_exp2f(__builtin_fmaf(bf2f((bf16_t)(w[q] & 0xFFFFu)), L2E, -mxl)) +
+                       __builtin_amdgcn_exp2f(__builtin_fmaf(bf2f((bf16_t)(w[q] >> 16)), L2E, -mxl));
         }
     }
     sum = block_reduce(sum, false, sh);
     const int lab = labels[m];
-    const float inv = 1.0f / sum;
+    const float sinv = s / sum;
     if (threadIdx.x == 0) row_loss[m] = s * (logf(sum) + mx - bf2f(row[lab]));
     __syncthreads();                                   // the label's logit is read before the row is overwritten
+    const int labc = lab >> 3;                         // the one chunk whose output also carries the -s of the one-hot
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
         const int c = threadIdx.x + 256 * i;
         if (c < nchunks) {
             const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-            uint32_t o[4];
+            float p[8];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int v = 8 * c + 2 * q;
-                const float p0 = __expf(bf2f((bf16_t)(w[q] & 0xFFFFu)) - mx) * inv;
-                const float p1 = __expf(bf2f((bf16_t)(w[q] >> 16)) - mx) * inv;
-                o[q] = pack_bf2(s * (p0 - (v == lab ? 1.0f : 0.0f)), s * (p1 - (v + 1 == lab ? 1.0f : 0.0f)));
+                p[2 * q] = __builtin_amdgcn_exp2f(__builtin_fmaf(bf2f((bf16_t)(w[q] & 0xFFFFu)), L2E, -mxl)) * sinv;
+                p[2 * q + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(bf2f((bf16_t)(w[q] >> 16)), L2E, -mxl)) * sinv;
             }
-            *reinterpret_cast<uint4*>(row + 8 * c) = make_uint4(o[0], o[1], o[2], o[3]);
+            if (c == labc) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[e] -= (e == (lab & 7)) ? s : 0.0f;
+            }
+            *reinterpret_cast<uint4*>(row + 8 * c) = make_uint4(pack_bf2(p[0], p[1]), pack_bf2(p[2], p[3]), pack_bf2(p[4], p[5]), pack_bf2(p[6], p[7]));
         }
     }
 }

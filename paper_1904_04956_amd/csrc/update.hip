@@ -91,6 +91,75 @@ __global__ __launch_bounds__(UPD_THREADS) void mix_kernel(MixPairs p, size_t n) 
     }
 }
 
+// Eq. 4 in one pass for a pair: theta_i' = theta_i - lr g_i, theta_j' likewise (Eq. 1c, same arithmetic
+// as sgd_kernel, momentum included), then both become (theta_i' + theta_j')/2.  One read of each
+// operand and one write of each result: 24 B per parameter of the pair against 40 B for sgd_kernel
+// twice plus mix_kernel (fp32, no momentum).
+template <bool SHADOW, bool MOM>
+__global__ __launch_bounds__(UPD_THREADS) void sgd_mix_pair_kernel(float* __restrict__ ti, float* __restrict__ tj,
+                                                                   const float* __restrict__ gi, const float* __restrict__ gj,
+                                                                   float* __restrict__ vi, float* __restrict__ vj,
+                                                                   unsigned short* __restrict__ si, unsigned short* __restrict__ sj,
+                                                                   size_t n, float lr, float mu) {
+    const size_t n4 = n / 4;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 a = reinterpret_cast<const float4*>(ti)[i];
+        float4 b = reinterpret_cast<const float4*>(tj)[i];
+        float4 ga = reinterpret_cast<const float4*>(gi)[i];
+        float4 gb = reinterpret_cast<const float4*>(gj)[i];
+        if (MOM) {
+            const float4 va = reinterpret_cast<const float4*>(vi)[i];
+            const float4 vb = reinterpret_cast<const float4*>(vj)[i];
+            ga.x = mu * va.x + ga.x; ga.y = mu * va.y + ga.y; ga.z = mu * va.z + ga.z; ga.w = mu * va.w + ga.w;
+            gb.x = mu * vb.x + gb.x; gb.y = mu * vb.y + gb.y; gb.z = mu * vb.z + gb.z; gb.w = mu * vb.w + gb.w;
+            reinterpret_cast<float4*>(vi)[i] = ga;
+            reinterpret_cast<float4*>(vj)[i] = gb;
+        }
+        a.x -= lr * ga.x; a.y -= lr * ga.y; a.z -= lr * ga.z; a.w -= lr * ga.w;
+        b.x -= lr * gb.x; b.y -= lr * gb.y; b.z -= lr * gb.z; b.w -= lr * gb.w;
+        float4 m;
+        m.x = 0.5f * (a.x + b.x); m.y = 0.5f * (a.y + b.y); m.z = 0.5f * (a.z + b.z); m.w = 0.5f * (a.w + b.w);
+        reinterpret_cast<float4*>(ti)[i] = m;
+        reinterpret_cast<float4*>(tj)[i] = m;
+        if (SHADOW) { const uint2 q = pack4(m); reinterpret_cast<uint2*>(si)[i] = q; reinterpret_cast<uint2*>(sj)[i] = q; }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const size_t i = n4 * 4 + threadIdx.x;
+        float ga = gi[i], gb = gj[i];
+        if (MOM) { ga = mu * vi[i] + ga; vi[i] = ga; gb = mu * vj[i] + gb; vj[i] = gb; }
+        const float a = ti[i] - lr * ga, b = tj[i] - lr * gb;
+        const float m = 0.5f * (a + b);
+        ti[i] = m; tj[i] = m;
+        if (SHADOW) { si[i] = f2bf(m); sj[i] = f2bf(m); }
+    }
+}
+
+// Every replica becomes the mean of all R replicas, summed in the order r = 0, 1, .., R-1 in float and
+// scaled by 1/R once (the in-HBM form of "allreduce(W') / lambda").
+template <bool SHADOW>
+__global__ __launch_bounds__(UPD_THREADS) void sync_average_kernel(ReplicaSet p, size_t n, float inv_r) {
+    const size_t n4 = n / 4;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        f32x4_t acc = reinterpret_cast<const f32x4_t*>(p.t[0])[i];
+        for (int r = 1; r < p.R; ++r) acc += reinterpret_cast<const f32x4_t*>(p.t[r])[i];
+        acc *= inv_r;
+        u32x2_t q; q[0] = pack_bf2(acc[0], acc[1]); q[1] = pack_bf2(acc[2], acc[3]);
+        for (int r = 0; r < p.R; ++r) {
+            reinterpret_cast<f32x4_t*>(p.t[r])[i] = acc;
+            if (SHADOW) reinterpret_cast<u32x2_t*>(p.s[r])[i] = q;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const size_t i = n4 * 4 + threadIdx.x;
+        float acc = p.t[0][i];
+        for (int r = 1; r < p.R; ++r) acc += p.t[r][i];
+        acc *= inv_r;
+        for (int r = 0; r < p.R; ++r) { p.t[r][i] = acc; if (SHADOW) p.s[r][i] = f2bf(acc); }
+    }
+}
+
 __global__ __launch_bounds__(UPD_THREADS) void shadow_kernel(const float* __restrict__ theta, unsigned short* __restrict__ shadow, size_t n) {
     const size_t n4 = n / 4;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -128,6 +197,27 @@ hipError_t launch_mix(const MixPairs& p, size_t n, hipStream_t st) {
     dim3 grid(per_pair, (unsigned)p.npairs), block(UPD_THREADS);
     if (p.sa[0]) hipLaunchKernelGGL(mix_kernel<true>, grid, block, 0, st, p, n);
     else hipLaunchKernelGGL(mix_kernel<false>, grid, block, 0, st, p, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_sgd_mix_pair(float* ti, float* tj, const float* gi, const float* gj, float* vi, float* vj,
+                               unsigned short* si, unsigned short* sj, size_t n, float lr, float mu, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    dim3 grid(blocks_for(n / 4, 256 * 16)), block(UPD_THREADS);
+    const bool mom = (mu != 0.0f), sh = si != nullptr;
+    if (sh && mom) hipLaunchKernelGGL((sgd_mix_pair_kernel<true, true>), grid, block, 0, st, ti, tj, gi, gj, vi, vj, si, sj, n, lr, mu);
+    else if (sh) hipLaunchKernelGGL((sgd_mix_pair_kernel<true, false>), grid, block, 0, st, ti, tj, gi, gj, vi, vj, si, sj, n, lr, mu);
+    else if (mom) hipLaunchKernelGGL((sgd_mix_pair_kernel<false, true>), grid, block, 0, st, ti, tj, gi, gj, vi, vj, si, sj, n, lr, mu);
+    else hipLaunchKernelGGL((sgd_mix_pair_kernel<false, false>), grid, block, 0, st, ti, tj, gi, gj, vi, vj, si, sj, n, lr, mu);
+    return hipGetLastError();
+}
+
+hipError_t launch_sync_average(const ReplicaSet& p, size_t n, hipStream_t st) {
+    if (n == 0 || p.R < 1) return hipSuccess;
+    dim3 grid(blocks_for(n / 4, 256 * 16)), block(UPD_THREADS);
+    const float inv_r = 1.0f / (float)p.R;
+    if (p.s[0]) hipLaunchKernelGGL(sync_average_kernel<true>, grid, block, 0, st, p, n, inv_r);
+    else hipLaunchKernelGGL(sync_average_kernel<false>, grid, block, 0, st, p, n, inv_r);
     return hipGetLastError();
 }
 

@@ -122,3 +122,45 @@ def mix(learners, partner, stream=None):
     masters = [l.theta for l in learners]
     shadows = [l.shadow for l in learners] if learners[0].shadow is not None else None
     bl.adpsgd_mix(masters, shadows, learners[0].n, len(learners), partner, stream)
+
+
+# ---- the strategies of section 3.2 as orders of the library's calls, R learners in one GPU's memory ----
+
+def adpsgd_step(learners, lr, partner, fused=False, stream=None):
+    """Eq. 4 in the synchronous order: g_i = calGrad(W_i), W_i' = apply(W_i, g_i), then the pairs average.
+    With fused=True each pair's update and average are one pass over the weights (sgd_mix_pair)."""
+    for l in learners:
+        l.calgrad(stream)
+    if not fused:
+        for l in learners:
+            l.apply(lr, stream)
+        mix(learners, partner, stream)
+        return
+    for i, j in enumerate(partner):
+        a = learners[i]
+        if j == i:
+            a.apply(lr, stream)
+        elif j > i:
+            b = learners[j]
+            bl.sgd_mix_pair(a.theta, b.theta, a.shadow, b.shadow, a.grad, b.grad, a.n, lr, a.momentum,
+                            a.velocity, b.velocity, stream)
+
+
+def stale_adpsgd_step(learners, lr, partner, stream=None):
+    """The integration order of Fig. 3b: the gradient is computed on the learner's own weights, the
+    weights are then replaced by the pair's average (pull) and the gradient is applied to that."""
+    for l in learners:
+        l.calgrad(stream)
+    mix(learners, partner, stream)
+    for l in learners:
+        l.apply(lr, stream)
+
+
+def sync_step(learners, lr, stream=None):
+    """SYNC of Fig. 3a: every learner applies its own gradient, then all take the mean of the results."""
+    for l in learners:
+        l.calgrad(stream)
+        l.apply(lr, stream)
+    masters = [l.theta for l in learners]
+    shadows = [l.shadow for l in learners] if learners[0].shadow is not None else None
+    bl.sync_average(masters, shadows, learners[0].n, len(learners), stream)

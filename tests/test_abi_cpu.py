@@ -133,3 +133,32 @@ def test_profile_names():
     names = [L.blstm_profile_name(i).decode() for i in range(k)]
     assert len(set(names)) == k and all(names)
     assert L.blstm_profile_name(k) == b""
+
+
+def test_lr_schedule_matches_the_oracle():
+    # section 3.1's recipe, evaluated by the library on the host, against the oracle's closed form
+    for base, peak in ((0.1, 1.0), (0.1, 0.1), (0.05, 0.8)):
+        for epoch in range(1, 21):
+            assert bl.blstm_lr_schedule(epoch, base, peak) == pytest.approx(orc.lr_schedule(epoch, base, peak), rel=1e-12)
+    assert bl.blstm_lr_schedule(3, 0.1, 1.0, warmup_epochs=1, anneal_from=2) == pytest.approx(orc.lr_schedule(3, 0.1, 1.0, 1, 2), rel=1e-12)
+
+
+def test_pair_and_average_validation():
+    # rejected on the host before anything is launched (no GPU needed)
+    L = bl.lib()
+    a, b, ga, gb = 4096, 8192, 12288, 16384
+    assert L.sgd_mix_pair(None, b, None, None, ga, gb, 16, 0.1, 0.0, None, None, None) == -1
+    assert L.sgd_mix_pair(a, b, None, None, ga, gb, 16, 0.1, 0.9, None, None, None) == -1       # momentum without velocities
+    assert L.sgd_mix_pair(a, b, 20480, None, ga, gb, 16, 0.1, 0.0, None, None, None) == -1       # one bf16 copy only
+    assert L.sgd_mix_pair(a, a, None, None, ga, gb, 16, 0.1, 0.0, None, None, None) == -2
+    assert L.sgd_mix_pair(a, b + 4, None, None, ga, gb, 16, 0.1, 0.0, None, None, None) == -4
+    assert L.sgd_mix_pair(a, b, None, None, ga, gb, 0, 0.1, 0.0, None, None, None) == 0         # n == 0: nothing to do
+    ptrs = (ctypes.c_void_p * 4)(4096, 8192, 12288, 16384)
+    assert L.sync_average(None, None, 16, 4, None) == -1
+    assert L.sync_average(ptrs, None, 16, 0, None) == -2
+    assert L.sync_average(ptrs, None, 16, 65, None) == -2
+    same = (ctypes.c_void_p * 4)(4096, 8192, 4096, 16384)
+    assert L.sync_average(same, None, 16, 4, None) == -2
+    odd = (ctypes.c_void_p * 4)(4096, 8196, 12288, 16384)
+    assert L.sync_average(odd, None, 16, 4, None) == -4
+    assert L.sync_average(ptrs, None, 0, 4, None) == 0

@@ -434,3 +434,66 @@ def test_lr_schedule_matches_section_3_1():
     assert orc.lr_schedule(12, base, base) == pytest.approx(base / 2)
     # linear scaling with the batch size: 0.1 at 256 -> 1.0 at 2560
     assert inputs.WORKLOADS["largebatch"].lr == pytest.approx(0.8)
+
+
+def test_fused_pair_by_hand_and_as_two_calls():
+    # Eq. 4 on scalars: theta_i = 1, theta_j = 3, g_i = 2, g_j = -4, lr = 0.5: theta_i' = 0, theta_j' = 5, average 2.5
+    m, vi, vj = orc.sgd_mix_pair(np.array([1.0]), np.array([3.0]), np.array([2.0]), np.array([-4.0]), 0.5)
+    assert m[0] == 2.5 and vi is None and vj is None
+    # with momentum 0.9 and velocities 1 and -1: v_i = 0.9 + 2 = 2.9, v_j = -0.9 - 4 = -4.9;
+    # theta_i' = 1 - 1.45 = -0.45, theta_j' = 3 + 2.45 = 5.45, average 2.5
+    m, vi, vj = orc.sgd_mix_pair(np.array([1.0]), np.array([3.0]), np.array([2.0]), np.array([-4.0]), 0.5, 0.9,
+                                 np.array([1.0]), np.array([-1.0]))
+    assert m[0] == pytest.approx(2.5) and vi[0] == pytest.approx(2.9) and vj[0] == pytest.approx(-4.9)
+    # Eq. 4 conserves the pair's sum of updated weights, and equal gradients on equal weights change nothing else
+    rng = np.random.default_rng(3)
+    a, b, ga, gb = (rng.standard_normal(50) for _ in range(4))
+    m, _, _ = orc.sgd_mix_pair(a, b, ga, gb, 0.3)
+    assert np.allclose(2 * m, (a - 0.3 * ga) + (b - 0.3 * gb), rtol=0, atol=1e-15)
+    m2, _, _ = orc.sgd_mix_pair(a, a, ga, ga, 0.3)
+    assert np.allclose(m2, a - 0.3 * ga, rtol=0, atol=1e-15)
+
+
+def test_sync_average_is_the_uniform_mixing_matrix_and_the_gradient_average():
+    rng = np.random.default_rng(4)
+    R, n, lr = 6, 40, 0.2
+    theta = rng.standard_normal(n)
+    grads = [rng.standard_normal(n) for _ in range(R)]
+    updated = [theta - lr * g for g in grads]
+    out = orc.sync_average(updated)
+    # every learner holds the same vector: the single step with the averaged gradient (section 3.2, SYNC)
+    one = theta - lr * np.mean(np.stack(grads), axis=0)
+    assert all(np.allclose(o, one, rtol=0, atol=1e-14) for o in out)
+    # as a matrix: W = (1/R) 1 1^T, doubly stochastic and symmetric, applied to the stacked replicas
+    W = np.full((R, R), 1.0 / R)
+    assert np.allclose(W @ np.stack(updated), np.stack(out), rtol=0, atol=1e-14)
+    # two replicas: SYNC and the ADPSGD pair average coincide
+    two = orc.sync_average(updated[:2])
+    pair = orc.adpsgd_mix(updated[:2], [1, 0])
+    assert np.array_equal(two[0], pair[0]) and np.array_equal(two[1], pair[1])
+
+
+def test_stale_adpsgd_order_by_hand_and_its_reductions():
+    # two learners on the quadratic E_i = (w - c_i)^2 / 2 (gradient w - c_i), lr = 0.5, c = (0, 4), w = (2, 6):
+    # g = (2, 2); pull: both hold 4; apply: (4 - 1, 4 - 1) = (3, 3)
+    w = [np.array([2.0]), np.array([6.0])]
+    c = [np.array([0.0]), np.array([4.0])]
+    g = [w[i] - c[i] for i in range(2)]
+    out = orc.stale_adpsgd_step(w, g, [1, 0], 0.5)
+    assert out[0][0] == 3.0 and out[1][0] == 3.0
+    # the synchronous order of Eq. 4 (apply, then average) gives (2 - 1 + 6 - 1) / 2 = 3 as well on this
+    # linear-gradient example at the first step; at the second step the two orders differ:
+    # stale: g = (3, -1), pull 3, apply (1.5, 3.5);  synchronous: apply (1.5, 3.5), average 2.5
+    g2 = [out[i] - c[i] for i in range(2)]
+    st = orc.stale_adpsgd_step(out, g2, [1, 0], 0.5)
+    assert st[0][0] == 1.5 and st[1][0] == 3.5
+    sy, _, _ = orc.sgd_mix_pair(out[0], out[1], g2[0], g2[1], 0.5)
+    assert sy[0] == 2.5
+    # identical learners: averaging changes nothing, so the stale order is plain SGD (Eq. 1c)
+    rng = np.random.default_rng(5)
+    a, ga = rng.standard_normal(30), rng.standard_normal(30)
+    same = orc.stale_adpsgd_step([a, a.copy()], [ga, ga.copy()], [1, 0], 0.1)
+    assert np.allclose(same[0], a - 0.1 * ga, rtol=0, atol=1e-15) and np.array_equal(same[0], same[1])
+    # lr = 0: pure mixing
+    mixed = orc.stale_adpsgd_step([a, ga], [a, a], [1, 0], 0.0)
+    assert np.array_equal(mixed[0], (a + ga) / 2)
