@@ -421,3 +421,11 @@ def test_adpsgd_workload_first_step_full_size():
     # one learner of the ADPSGD workload (batch 128 of the paper-shaped model) against the oracle in full
     w = inputs.WORKLOADS["adpsgd16"]
     check_step(w.dims(), 1, seed=5000, lr=w.lr)
+
+
+def test_paper_6x512_model_full_size():
+    # the model the paper trains and times (section 4.2): six layers of 512 cells per direction, batch 256
+    w = inputs.WORKLOADS["paper6x512"]
+    sample = [0, 31, 32, 100, 255]
+    d, theta, x, labels, loss, g = _sampled_forward_check(w, w.B, sample, 2e-2)
+    _parts_property_check(w, d, theta, x, labels, loss, g, parts=4, tol=2e-2)
