@@ -70,6 +70,7 @@ struct blstm_ctx {
     char* ws;
     size_t ws_bound;
     bool have_forward;
+    std::vector<char> fwd_persistent;   // per layer: the forward pass ran the persistent kernel (whose saved gates only its backward twin reads)
     // profiling
     bool prof;
     std::vector<ProfRec> recs;
@@ -202,6 +203,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     c->wROWLOSS = w; w += up256(M * 4);
     // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
     c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false;
+    c->fwd_persistent.assign(c->L, 0);
     c->wUHT = w; c->wCNT = w; c->wHX = w; c->wDAX = w; c->hx_bytes = 0; c->dax_bytes = 0;
     if (c->st == DT_BF16 && rec_waves_for(c->H, c->B) > 0) {
         const int NU = c->H / 32, tiles = (c->B + 31) / 32;
@@ -323,6 +325,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
             d.bias = at(theta, ctx->off_b[0][l], e); d.sBias = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);
             RUN(PC_GEMM_INPUT, "input projection", launch_gemm(d, st));
         }
+        ctx->fwd_persistent[l] = 0;
         if (ctx->rec_nbg > 0 && ctx->rec_path == 0) {   // all T frames of both directions in one launch
             unsigned* cnt = reinterpret_cast<unsigned*>(ctx->ws + ctx->wCNT);
             const int ncnt = 2 * ctx->rec_nbg * ctx->rec_tiles;
@@ -341,6 +344,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
             bool launched = false;
             RUN(PC_REC_FWD, "persistent recurrent forward", launch_rec_fwd(a, ctx->rec_sync == 1, st, &launched));
+            ctx->fwd_persistent[l] = launched ? 1 : 0;
             if (launched) continue;
         }
         for (int n = 0; n < T; ++n) {
@@ -459,7 +463,8 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
         return d;
     };
     bool wg_pending[2] = {false, false};
-    const bool persistent = ctx->rec_nbg > 0 && ctx->rec_path == 0;
+    bool persistent = false;                            // some layer's forward pass ran the persistent kernel
+    for (int l = 0; l < ctx->L; ++l) persistent = persistent || ctx->fwd_persistent[l] != 0;
     const bool sentinel = persistent && ctx->rec_sync == 1;
     if (persistent) {                                    // U_h^T of every layer and direction in one launch
         TransposeUhArgs ta{};
@@ -517,8 +522,10 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             HIPCHK("fill", hipStreamWaitEvent(st, ctx->ev_fill, 0));
             fill_pending = false;
         }
+        // The layer's backward recurrence takes the path its forward recurrence took: the two persistent
+        // kernels share the order of the saved gates, the per-frame kernels theirs.
         bool rec_done = false;
-        if (ctx->rec_nbg > 0 && ctx->rec_path == 0) {
+        if (ctx->fwd_persistent[l]) {
             unsigned* cnt = reinterpret_cast<unsigned*>(ctx->ws + ctx->wCNT);
             const int ncnt = 2 * ctx->rec_nbg * ctx->rec_tiles;
             unsigned short* uht0 = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wUHT) + (size_t)l * 2 * 4 * H * H;
@@ -533,6 +540,8 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
             RUN(PC_REC_BWD, "persistent recurrent backward", launch_rec_bwd(a, ctx->rec_sync == 1, st, &rec_done));
+            if (!rec_done)
+                return fail(BLSTM_ERR_HIP, "blstm_backward: the persistent kernel that must follow its forward twin cannot be launched");
         }
         for (int n = T - 1; n >= 0 && !rec_done; --n) {
             const int t[2] = {n, T - 1 - n};

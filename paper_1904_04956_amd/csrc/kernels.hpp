@@ -42,7 +42,7 @@ struct RecFwdArgs {
     const float* ax;              // W_x x + b for every frame, [M][8H]
     unsigned short* y;            // layer output h, [M][2H]
     unsigned short* hx;           // h again in exchange order, [T][2][tiles][H/16][2][32][8]; pre-filled with 0xFFFF in sentinel mode
-    unsigned short* gates;        // gate activations, [M][8H]
+    unsigned short* gates;        // gate activations for rec_bwd_kernel only, [M][2][H][4 gates] (not the per-frame path's [M][8H])
     float* c;                     // cell state, [M][2H]
     unsigned* cnt;                // [2*nbg][tiles_per_group] counters, zero before the launch
     unsigned* abort_word;         // raised when a wait ran out of time
@@ -52,7 +52,7 @@ struct RecFwdArgs {
 struct RecBwdArgs {
     const unsigned short* uht[2]; // U_h^T per direction, [H][4H]
     const unsigned short* dy;     // dE/dh from above, [M][2H]
-    const unsigned short* gates;  // [M][8H]
+    const unsigned short* gates;  // as rec_fwd_kernel wrote them, [M][2][H][4 gates]
     const float* c;               // [M][2H]
     unsigned short* da;           // dE/da, [M][8H]
     unsigned short* dax;          // dE/da again in exchange order, [T][2][tiles][4H/16][2][32][8]; pre-filled with 0xFFFF in sentinel mode

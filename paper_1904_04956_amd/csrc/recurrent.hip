@@ -234,7 +234,8 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     const int rb = 2 * EPT * wave + 4 * lh;
     auto re = [](int e) { return 8 * (e >> 2) + (e & 3); };
     const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // into [.][2H] tensors (h, c)
-    const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // into [.][8H] tensors (a_x, gates)
+    const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // into the row-major [.][8H] tensor (a_x)
+    const unsigned ogb = (unsigned)(rb * 8 * H + (d * H + j) * 4); // into the saved gates, [.][2][H][4]
     const int NT = (B + 31) / 32;                        // 32-row tiles of the batch
     constexpr int XH = H / 16 * XPAIR;                   // exchange elements per (frame, direction, tile)
     const unsigned ohp = (unsigned)(wave * (KW / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
@@ -388,8 +389,8 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             if (FULL || b0 + rb + re(e) < B) {
                 cb[o2b + (unsigned)(re(e) * 2 * H)] = cn[e];
                 yb[o2b + (unsigned)(re(e) * 2 * H)] = f2bf(hn[e]);
-                bf16_t* gp = gb + (o8b + (unsigned)(re(e) * 8 * H));
-                gp[0] = f2bf(gi[e]); gp[(unsigned)H] = f2bf(gf[e]); gp[(unsigned)(2 * H)] = f2bf(gg[e]); gp[(unsigned)(3 * H)] = f2bf(go[e]);
+                // the four gate activations of a unit are one 8-byte word: [frame row][direction][unit][gate]
+                *reinterpret_cast<uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) = make_uint2(pack_bf2(gi[e], gf[e]), pack_bf2(gg[e], go[e]));
             }
         }
         // next item's inputs; with one tile per workgroup its previous cell state is the one just computed
@@ -436,14 +437,15 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     auto re = [](int e) { return 8 * (e >> 2) + (e & 3); };
     const unsigned o1b = (unsigned)(rb * H + j);                 // into [.][H] (carried dE/dc),
     const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // [.][2H] (c, dy)
-    const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // and [.][8H] tensors (gates, dE/da)
+    const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // the row-major [.][8H] tensor (dE/da)
+    const unsigned ogb = (unsigned)(rb * 8 * H + (d * H + j) * 4); // and the saved gates, [.][2][H][4]
     const int NT = (B + 31) / 32;
     constexpr int XA = 4 * H / 16 * XPAIR;               // exchange elements per (frame, direction, tile)
     const unsigned oap = (unsigned)(wave * (KWB / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
     const unsigned oxs = xoff(j, rb);                    // where this thread's dE/da of gate 0, row rb goes
 
     // Saved activations of an item, loaded one item ahead (raw bf16 for the gates and dy).
-    struct Inputs { bf16_t g[EPT][4]; bf16_t dy[EPT]; float c[EPT], cp[EPT], dcr[EPT]; };
+    struct Inputs { uint2 g[EPT]; bf16_t dy[EPT]; float c[EPT], cp[EPT], dcr[EPT]; };   // g: (i, f), (g, o) as bf16 pairs
     auto issue_inputs = [&](int item, Inputs& in) {
         const int ni = item / ntl, i = item - ni * ntl;
         const int n = T - 1 - ni;
@@ -460,8 +462,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         for (int e = 0; e < EPT; ++e) {
             const bool ok = FULL || b0 + rb + re(e) < B;
             const unsigned o2 = o2b + (unsigned)(re(e) * 2 * H);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) in.g[e][g] = ok ? gb[o8b + (unsigned)((re(e) * 8 + g) * H)] : (bf16_t)0;
+            in.g[e] = ok ? *reinterpret_cast<const uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) : make_uint2(0u, 0u);
             in.c[e] = ok ? cb[o2] : 0.0f;
             in.cp[e] = (ok && n > 0) ? cpb[o2] : 0.0f;
             in.dy[e] = ok ? dyb[o2] : (bf16_t)0;
@@ -575,7 +576,8 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         bf16_t* dxb = a.dax + ((size_t)(t * 2 + d) * NT + (b0 >> 5)) * XA;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            const float gi = bf2f(cur.g[e][0]), gf = bf2f(cur.g[e][1]), gg = bf2f(cur.g[e][2]), go = bf2f(cur.g[e][3]);
+            const float gi = bf2f((bf16_t)(cur.g[e].x & 0xFFFFu)), gf = bf2f((bf16_t)(cur.g[e].x >> 16));
+            const float gg = bf2f((bf16_t)(cur.g[e].y & 0xFFFFu)), go = bf2f((bf16_t)(cur.g[e].y >> 16));
             const float dht = dh[e] + bf2f(cur.dy[e]);
             const float tc = fast_tanh(cur.c[e]);
             const float dc = dht * go * (1.0f - tc * tc) + cur.dcr[e];
