@@ -142,13 +142,22 @@ __global__ __launch_bounds__(UPD_THREADS) void sync_average_kernel(ReplicaSet p,
     const size_t n4 = n / 4;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        f32x4_t acc = reinterpret_cast<const f32x4_t*>(p.t[0])[i];
-        for (int r = 1; r < p.R; ++r) acc += reinterpret_cast<const f32x4_t*>(p.t[r])[i];
+        // four replicas' loads in flight at a time, added in index order
+        f32x4_t acc = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p.t[0]) + i);
+        int r = 1;
+        for (; r + 3 < p.R; r += 4) {
+            const f32x4_t x0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p.t[r]) + i);
+            const f32x4_t x1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p.t[r + 1]) + i);
+            const f32x4_t x2 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p.t[r + 2]) + i);
+            const f32x4_t x3 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p.t[r + 3]) + i);
+            acc += x0; acc += x1; acc += x2; acc += x3;
+        }
+        for (; r < p.R; ++r) acc += __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p.t[r]) + i);
         acc *= inv_r;
         u32x2_t q; q[0] = pack_bf2(acc[0], acc[1]); q[1] = pack_bf2(acc[2], acc[3]);
-        for (int r = 0; r < p.R; ++r) {
-            reinterpret_cast<f32x4_t*>(p.t[r])[i] = acc;
-            if (SHADOW) reinterpret_cast<u32x2_t*>(p.s[r])[i] = q;
+        for (r = 0; r < p.R; ++r) {
+            __builtin_nontemporal_store(acc, reinterpret_cast<f32x4_t*>(p.t[r]) + i);
+            if (SHADOW) __builtin_nontemporal_store(q, reinterpret_cast<u32x2_t*>(p.s[r]) + i);
         }
     }
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
