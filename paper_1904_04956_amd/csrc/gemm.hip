@@ -30,7 +30,10 @@ template <typename T> struct Vec { };
 template <> struct Vec<float>  { static constexpr int N = 4; };
 template <> struct Vec<bf16_t> { static constexpr int N = 8; };
 
-__device__ __forceinline__ int swz(int row) { return ((row >> 2) ^ row) & 7; }
+// Chunk column of a row is XORed with swz(row).  Any eight consecutive rows (fragment reads), the rows
+// 4l + j and 8l + j of eight consecutive l (the two row-fast store patterns) and one row's eight chunks
+// (K-fast stores) all spread over the eight 16-byte columns.  Period 64 rows; swz(row + 32) = swz(row) ^ 4.
+__device__ __forceinline__ int swz(int row) { return ((row >> 3) ^ row) & 7; }
 
 struct Operand {
     const void* p;
@@ -168,12 +171,38 @@ __device__ __forceinline__ void gload_rowfast_fast(uint4 (&r)[NCH], const char* 
     }
 }
 
+// 16-bit elements, unguarded: a thread owns eight consecutive rows (ro = tid % (rows / 8)) and four
+// consecutive contraction elements (quad kq = tid / (rows / 8) of the slab's sixteen): four 16-byte
+// loads, each eight rows of one k.  (A wave-level load costs the memory pipeline about the same whatever
+// its width, so 16-byte loads halve what this form spends there compared with 8-byte ones.)
+__device__ __forceinline__ void gload_rowfast8(uint4 (&r)[4], const char* base, long long kstep, uint32_t voff) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(base + voff + i * kstep);
+        r[i] = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+}
+// ... transposed in registers to the 8-byte half (quad parity) of each row's chunk.  s8: byte offset of
+// row 8 ro, column 0 plus 8 * (kq & 1); kch = kq / 2; ro as above.
+__device__ __forceinline__ void sstore_rowfast8(uint4* s, const uint4 (&r)[4], int s8, int kch, int ro) {
+    char* sb = reinterpret_cast<char*>(s) + s8;
+    const uint32_t w[4][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
+                              {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w}};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {                        // row 8 ro + j: word j / 2 of every load, its half j % 2
+        const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+        const uint32_t lo = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
+        const uint32_t hi = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
+        *reinterpret_cast<uint2*>(sb + j * (CHUNKS * 16) + ((kch ^ ((ro ^ j) & 7)) << 4)) = make_uint2(lo, hi);
+    }
+}
+
 // LDS stores through offsets computed once per thread (uint4 units): soff for the K-fast form,
 // soffj[j] for row j of the four-row group of the row-fast form.
 template <int NCH, int RP>
 __device__ __forceinline__ void sstore_kfast_off(uint4* s, const uint4 (&r)[NCH], int soff) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) s[soff + i * RP * CHUNKS] = r[i];
+    for (int i = 0; i < NCH; ++i) s[(((i * RP) & 32) ? (soff ^ 4) : soff) + i * RP * CHUNKS] = r[i];   // swz(row + 32) = swz(row) ^ 4
 }
 template <typename T, int NCH, int PR>
 __device__ __forceinline__ void sstore_rowfast_off(uint4* s, const uint4 (&r)[NCH], const int (&soffj)[4]) {
@@ -217,8 +246,12 @@ __device__ __forceinline__ void mma(f32x16_t& acc, const uint4& a, const uint4& 
     }
 }
 
-template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS>
-__global__ __launch_bounds__(128 * WN, 2) void gemm_kernel(Params P) {
+// D = sets of staging registers = slabs the global loads run ahead.  Two leaves room for two workgroups per
+// CU; four is for launches with at most one workgroup per CU, which have nothing else to cover the
+// latency of their loads with and the whole register file to themselves.
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D>
+__global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P) {
+    static_assert(D == 2 || (D == 4 && FAST && WN == 2), "the deep pipeline exists for the unguarded 128x128 tile only");
     static_assert(WN == 2 || (FAST && !RS), "the eight-wave shape exists in the unguarded form only");
     constexpr int NT = 128 * WN;                        // threads: 2 x WN wavefronts
     constexpr int VEC = Vec<TI>::N;
@@ -311,14 +344,22 @@ __global__ __launch_bounds__(128 * WN, 2) void gemm_kernel(Params P) {
     }
     // per-thread global byte offsets of the unguarded loads
     constexpr int ES = (int)sizeof(TI);
-    const uint32_t voff_a = AT ? (uint32_t)(kch * VEC * a0.ld * ES + rsub * ES)
+    // 16-bit row-fast operands of the unguarded 128x128 kernel: eight rows x four k per thread (NT == 2 BM == 2 BN;
+    // the 256x256 tile has no registers to spare for it and keeps the four-row form)
+    constexpr bool OCT = FAST && sizeof(TI) == 2 && WN == 2;
+    static_assert(!OCT || (NT == 2 * BM && NT == 2 * BN), "the octet mapping needs two threads per tile row");
+    const int ro_a = tid % (BM / 8), kq_a = tid / (BM / 8), ro_b = tid % (BN / 8), kq_b = tid / (BN / 8);
+    const int s8_a = ro_a * 8 * CHUNKS * 16 + (kq_a & 1) * 8, s8_b = ro_b * 8 * CHUNKS * 16 + (kq_b & 1) * 8;
+    const uint32_t voff_a = (AT && OCT) ? (uint32_t)(kq_a * 4 * a0.ld * ES + ro_a * 8 * ES)
+                          : AT ? (uint32_t)(kch * VEC * a0.ld * ES + rsub * ES)
                                : (uint32_t)((tid >> 3) * a0.ld * ES + (tid & 7) * 16);
-    const uint32_t voff_b = BT ? (uint32_t)(kch * VEC * b0.ld * ES + rsub * ES)
+    const uint32_t voff_b = (BT && OCT) ? (uint32_t)(kq_b * 4 * b0.ld * ES + ro_b * 8 * ES)
+                          : BT ? (uint32_t)(kch * VEC * b0.ld * ES + rsub * ES)
                                : (uint32_t)((tid >> 3) * b0.ld * ES + (tid & 7) * 16);
 
-    // Two sets of staging registers: the loads of slab it + 2 are issued while slab it is multiplied
-    // and slab it + 1 (loaded one iteration earlier) waits in the other set for its LDS buffer.
-    uint4 ra0[NCA], rb0[NCB], ra1[NCA], rb1[NCB];
+    // D sets of staging registers: the loads of slab it + D are issued while slab it is multiplied and
+    // slabs it + 1 .. it + D - 1 (loaded in earlier iterations) wait in the other sets for their LDS buffer.
+    uint4 ra[D][NCA], rb[D][NCB];
     auto gload = [&](int it, uint4 (&ra)[NCA], uint4 (&rb)[NCB]) {
         const bool s = it >= ntiles[0];
         const int k0 = (it - (s ? ntiles[0] : 0)) * BK;
@@ -329,9 +370,11 @@ __global__ __launch_bounds__(128 * WN, 2) void gemm_kernel(Params P) {
             // (both segments of a two-segment product share their leading dimensions in this mode)
             const char* pa = static_cast<const char*>(oa.p);
             const char* pb = static_cast<const char*>(ob.p);
-            if constexpr (AT) gload_rowfast_fast<TI, NCA, PR>(ra, pa + ((long long)k0 * oa.ld + row0) * ES, oa.ld * ES, voff_a);
+            if constexpr (AT && OCT) gload_rowfast8(ra, pa + ((long long)k0 * oa.ld + row0) * ES, oa.ld * ES, voff_a);
+            else if constexpr (AT) gload_rowfast_fast<TI, NCA, PR>(ra, pa + ((long long)k0 * oa.ld + row0) * ES, oa.ld * ES, voff_a);
             else    gload_kfast_fast<TI, NCA>(ra, pa + ((long long)row0 * oa.ld + k0) * ES, RP * oa.ld * ES, voff_a);
-            if constexpr (BT) gload_rowfast_fast<TI, NCB, PR>(rb, pb + ((long long)k0 * ob.ld + col0) * ES, ob.ld * ES, voff_b);
+            if constexpr (BT && OCT) gload_rowfast8(rb, pb + ((long long)k0 * ob.ld + col0) * ES, ob.ld * ES, voff_b);
+            else if constexpr (BT) gload_rowfast_fast<TI, NCB, PR>(rb, pb + ((long long)k0 * ob.ld + col0) * ES, ob.ld * ES, voff_b);
             else    gload_kfast_fast<TI, NCB>(rb, pb + ((long long)col0 * ob.ld + k0) * ES, RP * ob.ld * ES, voff_b);
         } else {
             const int K = s ? K1 : K0;
@@ -344,31 +387,38 @@ __global__ __launch_bounds__(128 * WN, 2) void gemm_kernel(Params P) {
     auto sstore = [&](int buf, const uint4 (&ra)[NCA], const uint4 (&rb)[NCB]) {
         uint4* a_s = smem + buf * STAGE;
         uint4* b_s = a_s + BM * CHUNKS;
-        if constexpr (AT) sstore_rowfast_off<TI, NCA, PR>(a_s, ra, soff_r); else sstore_kfast_off<NCA, RP>(a_s, ra, soff_k);
-        if constexpr (BT) sstore_rowfast_off<TI, NCB, PR>(b_s, rb, soff_r); else sstore_kfast_off<NCB, RP>(b_s, rb, soff_k);
+        if constexpr (AT && OCT) sstore_rowfast8(a_s, ra, s8_a, kq_a >> 1, ro_a);
+        else if constexpr (AT) sstore_rowfast_off<TI, NCA, PR>(a_s, ra, soff_r);
+        else sstore_kfast_off<NCA, RP>(a_s, ra, soff_k);
+        if constexpr (BT && OCT) sstore_rowfast8(b_s, rb, s8_b, kq_b >> 1, ro_b);
+        else if constexpr (BT) sstore_rowfast_off<TI, NCB, PR>(b_s, rb, soff_r);
+        else sstore_kfast_off<NCB, RP>(b_s, rb, soff_k);
     };
+    // (rows 32 apart: the swizzle flips bit 2 of the chunk column, which is the offset of sub-step q ^ 2)
     auto lfrag = [&](const uint4* a_s, const uint4* b_s, int q, uint4 (&af)[TM], uint4 (&bf)[TN]) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = a_s[roff_a[q] + i * 32 * CHUNKS];
+        for (int i = 0; i < TM; ++i) af[i] = a_s[roff_a[(i & 1) ? (q ^ 2) : q] + i * 32 * CHUNKS];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bf[j] = b_s[roff_b[q] + j * 32 * CHUNKS];
+        for (int j = 0; j < TN; ++j) bf[j] = b_s[roff_b[(j & 1) ? (q ^ 2) : q] + j * 32 * CHUNKS];
     };
 
     const int nslab = it_end - it_begin;
     if (nslab > 0) {
-        gload(it_begin, ra0, rb0);
-        sstore(0, ra0, rb0);
-        if (nslab > 1) gload(it_begin + 1, ra1, rb1);
+        gload(it_begin, ra[0], rb[0]);
+        sstore(0, ra[0], rb[0]);
     }
+#pragma unroll
+    for (int u = 1; u < D; ++u)
+        if (nslab > u) gload(it_begin + u, ra[u], rb[u]);
     __syncthreads();
-    // slab j = it - it_begin lives in LDS buffer j & 1 and was staged through register set j & 1
-    // `steady`: slabs it + 1 and it + 2 exist for sure, so the loads and the LDS stores are unconditional
+    // slab j = it - it_begin lives in LDS buffer j & 1 and was staged through register set j % D
+    // `steady`: slabs it + 1 and it + D exist for sure, so the loads and the LDS stores are unconditional
     // (every path through the steady loop then has the same loads in flight, which lets the compiler
     // wait for exactly the older set before the stores).
     auto step = [&](int it, const bool steady, uint4 (&ra_cur)[NCA], uint4 (&rb_cur)[NCB], const uint4 (&ra_nxt)[NCA],
                     const uint4 (&rb_nxt)[NCB]) __attribute__((always_inline)) {
         const int buf = (it - it_begin) & 1;
-        if (steady || it + 2 < it_end) gload(it + 2, ra_cur, rb_cur);
+        if (steady || it + D < it_end) gload(it + D, ra_cur, rb_cur);
         const uint4* a_s = smem + buf * STAGE;
         const uint4* b_s = a_s + BM * CHUNKS;
         // the 64x64 wave tile keeps two sets of fragments in flight
@@ -392,13 +442,14 @@ __global__ __launch_bounds__(128 * WN, 2) void gemm_kernel(Params P) {
         __syncthreads();
     };
     int it = it_begin;
-    for (; it + 3 < it_end; it += 2) {
-        step(it, true, ra0, rb0, ra1, rb1);
-        step(it + 1, true, ra1, rb1, ra0, rb0);
+    for (; it + 2 * D - 1 < it_end; it += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) step(it + u, true, ra[u], rb[u], ra[(u + 1) % D], rb[(u + 1) % D]);
     }
-    for (; it < it_end; it += 2) {                        // the last one to three slabs
-        step(it, false, ra0, rb0, ra1, rb1);
-        if (it + 1 < it_end) step(it + 1, false, ra1, rb1, ra0, rb0);
+    for (; it < it_end; it += D) {                        // the last slabs
+#pragma unroll
+        for (int u = 0; u < D; ++u)
+            if (it + u < it_end) step(it + u, false, ra[u], rb[u], ra[(u + 1) % D], rb[(u + 1) % D]);
     }
 
     if (RS && do_rs && (lane & 31) == 0) {
@@ -529,43 +580,48 @@ int fast_flags(const void* p, long long ld, long long stride, int batch, bool ro
     return f;
 }
 
-template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS>
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D = 2>
 hipError_t launch_kernel(const Params& P, dim3 grid, hipStream_t stream) {
     constexpr size_t lds = 2 * (size_t)(64 * TM + 32 * TN * WN) * CHUNKS * 16;
     static thread_local bool attr_set = false;
     if (!attr_set && lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS>), grid, dim3(128 * WN), lds, stream, P);
+    hipLaunchKernelGGL((gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D>), grid, dim3(128 * WN), lds, stream, P);
     return hipGetLastError();
 }
 
 template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN>
-hipError_t launch_shape(const Params& P, bool fast, dim3 grid, hipStream_t stream) {
+hipError_t launch_shape(const Params& P, bool fast, bool deep, dim3 grid, hipStream_t stream) {
     if constexpr (WN != 2) {
         if (P.rowsum || !fast) return hipErrorInvalidValue;   // the large tile is built unguarded and without row sums
         return launch_kernel<TI, TO, AT, BT, TM, TN, WN, true, false>(P, grid, stream);
     } else {
         if constexpr (AT && BT) {
-            if (P.rowsum)
+            if (P.rowsum) {
+                if (fast && deep) return launch_kernel<TI, TO, AT, BT, TM, TN, WN, true, true, 4>(P, grid, stream);
                 return fast ? launch_kernel<TI, TO, AT, BT, TM, TN, WN, true, true>(P, grid, stream)
                             : launch_kernel<TI, TO, AT, BT, TM, TN, WN, false, true>(P, grid, stream);
+            }
         }
         if (P.rowsum) return hipErrorInvalidValue;           // row sums exist for the dA^T X form on 128x128 tiles only
+        if constexpr (AT && BT) {                             // (the deep pipeline is built for the dA^T X form, where it pays)
+            if (fast && deep) return launch_kernel<TI, TO, AT, BT, TM, TN, WN, true, false, 4>(P, grid, stream);
+        }
         return fast ? launch_kernel<TI, TO, AT, BT, TM, TN, WN, true, false>(P, grid, stream)
                     : launch_kernel<TI, TO, AT, BT, TM, TN, WN, false, false>(P, grid, stream);
     }
 }
 
 template <typename TI, typename TO, int TM, int TN, int WN>
-hipError_t launch_form(const GemmDesc& d, const Params& P, bool fast, dim3 grid, hipStream_t stream) {
-    if (!d.atrans && !d.btrans) return launch_shape<TI, TO, false, false, TM, TN, WN>(P, fast, grid, stream);
-    if (!d.atrans && d.btrans) return launch_shape<TI, TO, false, true, TM, TN, WN>(P, fast, grid, stream);
-    if (d.atrans && d.btrans) return launch_shape<TI, TO, true, true, TM, TN, WN>(P, fast, grid, stream);
-    return launch_shape<TI, TO, true, false, TM, TN, WN>(P, fast, grid, stream);
+hipError_t launch_form(const GemmDesc& d, const Params& P, bool fast, bool deep, dim3 grid, hipStream_t stream) {
+    if (!d.atrans && !d.btrans) return launch_shape<TI, TO, false, false, TM, TN, WN>(P, fast, deep, grid, stream);
+    if (!d.atrans && d.btrans) return launch_shape<TI, TO, false, true, TM, TN, WN>(P, fast, deep, grid, stream);
+    if (d.atrans && d.btrans) return launch_shape<TI, TO, true, true, TM, TN, WN>(P, fast, deep, grid, stream);
+    return launch_shape<TI, TO, true, false, TM, TN, WN>(P, fast, deep, grid, stream);
 }
 
 // The unguarded kernel applies when every tile is full, every segment's K is a whole number of
@@ -616,7 +672,7 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     hipError_t e;
     if (plan.splits > 1) {
         // partial tiles are float whatever the output type
-        e = plan.big_tile ? launch_form<TI, float, 4, 2, 4>(d, P, fast, grid, stream) : launch_form<TI, float, 2, 2, 2>(d, P, fast, grid, stream);
+        e = plan.big_tile ? launch_form<TI, float, 4, 2, 4>(d, P, fast, false, grid, stream) : launch_form<TI, float, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
         if (e != hipSuccess) return e;
         const long long total = (long long)d.M * d.N;
         unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
@@ -625,13 +681,13 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
                            P.rs_partial, d.rowsum, d.sRowsum);
         return hipGetLastError();
     }
-    return plan.big_tile ? launch_form<TI, TO, 4, 2, 4>(d, P, fast, grid, stream) : launch_form<TI, TO, 2, 2, 2>(d, P, fast, grid, stream);
+    return plan.big_tile ? launch_form<TI, TO, 4, 2, 4>(d, P, fast, false, grid, stream) : launch_form<TI, TO, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
 }
 
 }  // namespace
 
 GemmPlan plan_gemm(const GemmDesc& d) {
-    GemmPlan p{false, 1, 0};
+    GemmPlan p{false, false, 1, 0};
     const int batch = d.batch > 0 ? d.batch : 1;
     const long long t256 = (long long)((d.M + 255) / 256) * ((d.N + 255) / 256) * batch;
     const long long t128 = (long long)((d.M + 127) / 128) * ((d.N + 127) / 128) * batch;
@@ -660,6 +716,11 @@ GemmPlan plan_gemm(const GemmDesc& d) {
             p.partial_bytes = need;
         }
     }
+    // at most one 128x128 workgroup per CU: run the loads four slabs ahead instead of two
+#ifndef GEMM_DEEP_LIMIT
+#define GEMM_DEEP_LIMIT 256
+#endif
+    p.deep = t128 * p.splits <= GEMM_DEEP_LIMIT;
     return p;
 }
 

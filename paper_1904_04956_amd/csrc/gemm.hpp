@@ -38,6 +38,7 @@ struct GemmDesc {
 // How a product is run: 256x256 or 128x128 tiles, and into how many K ranges it is split.
 struct GemmPlan {
     bool big_tile;
+    bool deep;                // 128x128 tile with the loads four slabs ahead (launches of at most one workgroup per CU)
     int splits;
     size_t partial_bytes;     // scratch the split needs (0 when splits == 1)
 };
