@@ -40,13 +40,15 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(TS* u, long long ldu,
     }
 }
 
-// bf16 rows that fit the registers of one workgroup (V <= 256 * 8 * NC, V a multiple of 8, rows
+// bf16 rows that fit the registers of one workgroup (V <= NT * 8 * NC, V a multiple of 8, rows
 // 16-byte aligned): the row is read once with 16-byte loads, kept in registers as packed bf16,
 // reduced, and written back as dE/du with 16-byte stores.  HBM traffic: one read and one write.
-template <int NC>
-__global__ __launch_bounds__(256) void softmax_rows_bf16_regs_kernel(bf16_t* u, long long ldu, const int32_t* labels,
+// A long row is spread over more threads rather than more registers per thread, so that several
+// rows per CU are in flight and one row's loads and stores run under another's arithmetic.
+template <int NC, int NT>
+__global__ __launch_bounds__(NT) void softmax_rows_bf16_regs_kernel(bf16_t* u, long long ldu, const int32_t* labels,
                                                                       float* row_loss, int V, float s) {
-    __shared__ float sh[4];
+    __shared__ float sh[NT / 64];
     const int m = blockIdx.x;
     bf16_t* row = u + (long long)m * ldu;
     const int nchunks = V >> 3;
@@ -54,7 +56,7 @@ __global__ __launch_bounds__(256) void softmax_rows_bf16_regs_kernel(bf16_t* u, 
     float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        const int c = threadIdx.x + 256 * i;
+        const int c = threadIdx.x + NT * i;
         if (c < nchunks) {
             r[i] = *reinterpret_cast<const uint4*>(row + 8 * c);
             const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(256) void softmax_rows_bf16_regs_kernel(bf16_t* u, 
     float sum = 0.0f;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        const int c = threadIdx.x + 256 * i;
+        const int c = threadIdx.x + NT * i;
         if (c < nchunks) {
             const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
 #pragma unroll
@@ -89,7 +91,7 @@ __global__ __launch_bounds__(256) void softmax_rows_bf16_regs_kernel(bf16_t* u, 
     const int labc = lab >> 3;                         // the one chunk whose output also carries the -s of the one-hot
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-        const int c = threadIdx.x + 256 * i;
+        const int c = threadIdx.x + NT * i;
         if (c < nchunks) {
             const uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
             float p[8];
@@ -123,9 +125,14 @@ hipError_t launch_softmax_rows(void* u, long long ldu, const int32_t* labels, fl
     if (store == DT_BF16) {
         bf16_t* ub = static_cast<bf16_t*>(u);
         const bool vec = (V % 8 == 0) && (ldu % 8 == 0) && (reinterpret_cast<uintptr_t>(u) % 16 == 0);
-        if (vec && V <= 256 * 8 * 4) hipLaunchKernelGGL(softmax_rows_bf16_regs_kernel<4>, dim3(M), dim3(256), 0, st, ub, ldu, labels, row_loss, V, s);
-        else if (vec && V <= 256 * 8 * 8) hipLaunchKernelGGL(softmax_rows_bf16_regs_kernel<8>, dim3(M), dim3(256), 0, st, ub, ldu, labels, row_loss, V, s);
-        else if (vec && V <= 256 * 8 * 16) hipLaunchKernelGGL(softmax_rows_bf16_regs_kernel<16>, dim3(M), dim3(256), 0, st, ub, ldu, labels, row_loss, V, s);
+        const int nchunks = V / 8;
+#define BLSTM_SOFTMAX_REGS(NC, NT) \
+    hipLaunchKernelGGL((softmax_rows_bf16_regs_kernel<NC, NT>), dim3(M), dim3(NT), 0, st, ub, ldu, labels, row_loss, V, s)
+        if (vec && nchunks <= 4 * 256) BLSTM_SOFTMAX_REGS(4, 256);
+        else if (vec && nchunks <= 4 * 512) BLSTM_SOFTMAX_REGS(4, 512);
+        else if (vec && nchunks <= 4 * 1024) BLSTM_SOFTMAX_REGS(4, 1024);
+        else if (vec && nchunks <= 8 * 1024) BLSTM_SOFTMAX_REGS(8, 1024);
+#undef BLSTM_SOFTMAX_REGS
         else hipLaunchKernelGGL(softmax_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, st, ub, ldu, labels, row_loss, V, s);
     }
     else

@@ -137,6 +137,13 @@ def test_shapes_bf16(dims):
     check_step(dims, 1, seed=78, theta_scale=2.0)
 
 
+@pytest.mark.parametrize("V", [8000, 12000, 12004, 40000, 70000])
+def test_softmax_row_widths_bf16(V):
+    # one softmax row kernel per range of V (256, 512, 1024 threads per row; rows too long or too
+    # ragged for the register-resident forms take the three-pass kernel)
+    check_step(dict(T=2, B=5, D=8, H=8, L=1, P=8, V=V), 1, seed=80, theta_scale=4.0)
+
+
 @pytest.mark.parametrize("dims", [
     dict(T=4, B=300, D=64, H=512, L=1, P=64, V=200),        # ten batch tiles over eight groups: two tiles per workgroup, some empty
     dict(T=6, B=45, D=32, H=256, L=2, P=0, V=120),          # two wavefronts per workgroup, ragged batch tile
