@@ -8,11 +8,12 @@
 // 16-byte chunks per row (64 bf16 or 32 float) is staged through LDS, double buffered, with the
 // next slab's global loads in flight while the current one is multiplied, and the fragments of
 // the next sub-step read from LDS while the current products issue.  Operands whose contraction
-// index is the slow one in memory ("transposed") are loaded along their fast index and
-// transposed in registers on the way to LDS, so all three forms of a training step's products
-// (X W^T, dA W, dA^T X) run through the same inner loop.  LDS rows are XOR-swizzled at chunk
-// granularity so that both the row-wise stores and the MFMA fragment reads spread over the
-// banks.  Products with a small output and a long contraction are split along K over
+// index is the slow one in memory ("transposed") are loaded along their fast index, so all three
+// forms of a training step's products (X W^T, dA W, dA^T X) run through the same inner loop:
+// 16-bit ones of full tiles stay in LDS as they lie in memory and are transposed by the LDS read
+// itself (ds_read_b64_tr_b16); the others are transposed in registers on the way to LDS.  LDS
+// rows are XOR-swizzled at chunk granularity so that both the stores and the MFMA fragment reads
+// spread over the banks.  Products with a small output and a long contraction are split along K over
 // blockIdx.y into float partial tiles that a second kernel sums in a fixed order.
 #include "common.hpp"
 #include "gemm.hpp"
@@ -39,7 +40,7 @@ struct Operand {
     const void* p;
     long long ld;
     int rows;       // extent of the non-contracted index (M for A, N for B)
-    int fast;       // bit 0: the widest vector load is legal; bit 1: 8-byte loads are legal (bf16, K fast)
+    int fast;       // bit 0: the widest vector load is legal; bit 1: 8-byte loads are legal (bf16, K fast); bit 2: 16-byte loads of eight rows (bf16, row fast)
 };
 
 struct Params {
@@ -171,30 +172,35 @@ __device__ __forceinline__ void gload_rowfast_fast(uint4 (&r)[NCH], const char* 
     }
 }
 
-// 16-bit elements, unguarded: a thread owns eight consecutive rows (ro = tid % (rows / 8)) and four
-// consecutive contraction elements (quad kq = tid / (rows / 8) of the slab's sixteen): four 16-byte
-// loads, each eight rows of one k.  (A wave-level load costs the memory pipeline about the same whatever
-// its width, so 16-byte loads halve what this form spends there compared with 8-byte ones.)
-__device__ __forceinline__ void gload_rowfast8(uint4 (&r)[4], const char* base, long long kstep, uint32_t voff) {
+// 16-bit operands whose non-contracted index is the fast one in memory, unguarded: the slab
+// stays in LDS as it lies in memory, [k][row] with 16-byte chunks of eight rows, and the LDS read that
+// feeds the matrix cores transposes it (ds_read_b64_tr_b16: sixteen lanes read a 4 x 16 block of 16-bit
+// elements, lane j of them receives column j).  No transposes in registers, plain 16-byte loads and stores.
+// CPR = chunks per k-row.  A thread owns chunk tid % CPR of the k-rows tid / CPR + 16 i.
+// Swizzle: the 32-byte pair of chunks p of k-row k sits at pair p ^ ((k & 3) << 1), so that the four k-rows
+// a group of sixteen lanes reads, and the neighbouring group's, fall on different banks.
+template <int NCH>
+__device__ __forceinline__ void gload_tr(uint4 (&r)[NCH], const char* base, long long pass_step, uint32_t voff) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(base + voff + i * kstep);
+    for (int i = 0; i < NCH; ++i) {
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(base + voff + i * pass_step);
         r[i] = make_uint4(v[0], v[1], v[2], v[3]);
     }
 }
-// ... transposed in registers to the 8-byte half (quad parity) of each row's chunk.  s8: byte offset of
-// row 8 ro, column 0 plus 8 * (kq & 1); kch = kq / 2; ro as above.
-__device__ __forceinline__ void sstore_rowfast8(uint4* s, const uint4 (&r)[4], int s8, int kch, int ro) {
-    char* sb = reinterpret_cast<char*>(s) + s8;
-    const uint32_t w[4][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
-                              {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w}};
+template <int NCH, int CPR>
+__device__ __forceinline__ void sstore_tr(uint4* s, const uint4 (&r)[NCH], int soff) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {                        // row 8 ro + j: word j / 2 of every load, its half j % 2
-        const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-        const uint32_t lo = __builtin_amdgcn_perm(w[1][j >> 1], w[0][j >> 1], sel);
-        const uint32_t hi = __builtin_amdgcn_perm(w[3][j >> 1], w[2][j >> 1], sel);
-        *reinterpret_cast<uint2*>(sb + j * (CHUNKS * 16) + ((kch ^ ((ro ^ j) & 7)) << 4)) = make_uint2(lo, hi);
-    }
+    for (int i = 0; i < NCH; ++i) s[soff + i * 16 * CPR] = r[i];
+}
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+// eight consecutive k of one row: two transposing reads, k-rows kb .. kb+3 and kb+4 .. kb+7 (ROWB bytes per k-row)
+template <int ROWB>
+__device__ __forceinline__ uint4 lfrag_tr(const char* s, int kb) {
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(s + kb * ROWB));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(s + (kb + 4) * ROWB));
+    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+    return make_uint4(l2.x, l2.y, h2.x, h2.y);
 }
 
 // LDS stores through offsets computed once per thread (uint4 units): soff for the K-fast form,
@@ -293,19 +299,30 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // Row sums of A ride along as one more product against a fragment of ones; only the
-    // workgroups of the first tile column, and in them the waves of the first half, do it.
+    // Row sums of A ride along on the vector ALU, which the loop leaves mostly idle: the waves of the first
+    // half of the workgroups of the first tile column add up the fragments they feed to the matrix cores
+    // (a lane holds eight consecutive k of one row; lanes l and l + 32 hold the two halves of a sub-step).
     // (RS is instantiated for the 128x128 shape with both operands transposed only: the
     // weight-gradient products are the ones that need row sums.)
     constexpr int NRS = RS ? TM : 1;
     const bool do_rs = RS && P.rowsum != nullptr && tn == 0 && wn == 0;
-    f32x16_t rs[NRS];
+    float rs[NRS];
 #pragma unroll
-    for (int i = 0; i < NRS; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) rs[i][e] = 0.0f;
-    const uint32_t one_w = sizeof(TI) == 2 ? 0x3F803F80u : 0x3F800000u;
-    const uint4 ones = make_uint4(one_w, one_w, one_w, one_w);
+    for (int i = 0; i < NRS; ++i) rs[i] = 0.0f;
+    auto add_row = [](float acc, const uint4& f) {
+        if constexpr (sizeof(TI) == 2) {
+            typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+            const bf16x2_t one = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, f.x), one, acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, f.y), one, acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, f.z), one, acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, f.w), one, acc, false);
+        } else {
+            acc += __builtin_bit_cast(float, f.x); acc += __builtin_bit_cast(float, f.y);
+            acc += __builtin_bit_cast(float, f.z); acc += __builtin_bit_cast(float, f.w);
+        }
+        return acc;
+    };
 
     int ntiles[2];
     ntiles[0] = (P.K[0] + BK - 1) / BK;
@@ -344,18 +361,30 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
     }
     // per-thread global byte offsets of the unguarded loads
     constexpr int ES = (int)sizeof(TI);
-    // 16-bit row-fast operands of the unguarded 128x128 kernel: eight rows x four k per thread (NT == 2 BM == 2 BN;
-    // the 256x256 tile has no registers to spare for it and keeps the four-row form)
-    constexpr bool OCT = FAST && sizeof(TI) == 2 && WN == 2;
-    static_assert(!OCT || (NT == 2 * BM && NT == 2 * BN), "the octet mapping needs two threads per tile row");
-    const int ro_a = tid % (BM / 8), kq_a = tid / (BM / 8), ro_b = tid % (BN / 8), kq_b = tid / (BN / 8);
-    const int s8_a = ro_a * 8 * CHUNKS * 16 + (kq_a & 1) * 8, s8_b = ro_b * 8 * CHUNKS * 16 + (kq_b & 1) * 8;
-    const uint32_t voff_a = (AT && OCT) ? (uint32_t)(kq_a * 4 * a0.ld * ES + ro_a * 8 * ES)
-                          : AT ? (uint32_t)(kch * VEC * a0.ld * ES + rsub * ES)
+    const uint32_t voff_a = AT ? (uint32_t)(kch * VEC * a0.ld * ES + rsub * ES)
                                : (uint32_t)((tid >> 3) * a0.ld * ES + (tid & 7) * 16);
-    const uint32_t voff_b = (BT && OCT) ? (uint32_t)(kq_b * 4 * b0.ld * ES + ro_b * 8 * ES)
-                          : BT ? (uint32_t)(kch * VEC * b0.ld * ES + rsub * ES)
+    const uint32_t voff_b = BT ? (uint32_t)(kch * VEC * b0.ld * ES + rsub * ES)
                                : (uint32_t)((tid >> 3) * b0.ld * ES + (tid & 7) * 16);
+
+    // transposing-read form (16-bit, unguarded): per-thread store offset, load offset, and the byte offsets of the
+    // fragment reads of each 32-row block (lane group g = lane / 16: rows 16 (g & 1) .., k-rows 8 (g / 2) ..)
+    constexpr bool TRP = FAST && sizeof(TI) == 2;
+    constexpr int CPR_A = BM / 8, CPR_B = BN / 8;
+    static_assert(!TRP || (NT / CPR_A == 16 && NT / CPR_B == 16), "a pass of loads covers sixteen k-rows");
+    auto tr_soff = [&](int cpr) { const int kt = tid / cpr, mc = tid % cpr; return kt * cpr + ((((mc >> 1) ^ ((kt & 3) << 1)) << 1) | (mc & 1)); };
+    const int soff_ta = tr_soff(CPR_A), soff_tb = tr_soff(CPR_B);
+    const uint32_t voff_ta = (uint32_t)((tid / CPR_A) * a0.ld * ES + (tid % CPR_A) * 16);
+    const uint32_t voff_tb = (uint32_t)((tid / CPR_B) * b0.ld * ES + (tid % CPR_B) * 16);
+    int troff_a[TM], troff_b[TN];
+    {
+        const int g = lane >> 4, li = lane & 15, sw = (li >> 2) << 1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            troff_a[i] = (8 * (g >> 1) + (li >> 2)) * (BM * 2) + (((wm * 2 * TM + 2 * i + (g & 1)) ^ sw) << 5) + (li & 3) * 8;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            troff_b[j] = (8 * (g >> 1) + (li >> 2)) * (BN * 2) + (((wn * 2 * TN + 2 * j + (g & 1)) ^ sw) << 5) + (li & 3) * 8;
+    }
 
     // D sets of staging registers: the loads of slab it + D are issued while slab it is multiplied and
     // slabs it + 1 .. it + D - 1 (loaded in earlier iterations) wait in the other sets for their LDS buffer.
@@ -370,10 +399,10 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
             // (both segments of a two-segment product share their leading dimensions in this mode)
             const char* pa = static_cast<const char*>(oa.p);
             const char* pb = static_cast<const char*>(ob.p);
-            if constexpr (AT && OCT) gload_rowfast8(ra, pa + ((long long)k0 * oa.ld + row0) * ES, oa.ld * ES, voff_a);
+            if constexpr (AT && TRP) gload_tr<NCA>(ra, pa + ((long long)k0 * oa.ld + row0) * ES, 16 * oa.ld * ES, voff_ta);
             else if constexpr (AT) gload_rowfast_fast<TI, NCA, PR>(ra, pa + ((long long)k0 * oa.ld + row0) * ES, oa.ld * ES, voff_a);
             else    gload_kfast_fast<TI, NCA>(ra, pa + ((long long)row0 * oa.ld + k0) * ES, RP * oa.ld * ES, voff_a);
-            if constexpr (BT && OCT) gload_rowfast8(rb, pb + ((long long)k0 * ob.ld + col0) * ES, ob.ld * ES, voff_b);
+            if constexpr (BT && TRP) gload_tr<NCB>(rb, pb + ((long long)k0 * ob.ld + col0) * ES, 16 * ob.ld * ES, voff_tb);
             else if constexpr (BT) gload_rowfast_fast<TI, NCB, PR>(rb, pb + ((long long)k0 * ob.ld + col0) * ES, ob.ld * ES, voff_b);
             else    gload_kfast_fast<TI, NCB>(rb, pb + ((long long)col0 * ob.ld + k0) * ES, RP * ob.ld * ES, voff_b);
         } else {
@@ -387,19 +416,25 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
     auto sstore = [&](int buf, const uint4 (&ra)[NCA], const uint4 (&rb)[NCB]) {
         uint4* a_s = smem + buf * STAGE;
         uint4* b_s = a_s + BM * CHUNKS;
-        if constexpr (AT && OCT) sstore_rowfast8(a_s, ra, s8_a, kq_a >> 1, ro_a);
+        if constexpr (AT && TRP) sstore_tr<NCA, CPR_A>(a_s, ra, soff_ta);
         else if constexpr (AT) sstore_rowfast_off<TI, NCA, PR>(a_s, ra, soff_r);
         else sstore_kfast_off<NCA, RP>(a_s, ra, soff_k);
-        if constexpr (BT && OCT) sstore_rowfast8(b_s, rb, s8_b, kq_b >> 1, ro_b);
+        if constexpr (BT && TRP) sstore_tr<NCB, CPR_B>(b_s, rb, soff_tb);
         else if constexpr (BT) sstore_rowfast_off<TI, NCB, PR>(b_s, rb, soff_r);
         else sstore_kfast_off<NCB, RP>(b_s, rb, soff_k);
     };
     // (rows 32 apart: the swizzle flips bit 2 of the chunk column, which is the offset of sub-step q ^ 2)
     auto lfrag = [&](const uint4* a_s, const uint4* b_s, int q, uint4 (&af)[TM], uint4 (&bf)[TN]) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = a_s[roff_a[(i & 1) ? (q ^ 2) : q] + i * 32 * CHUNKS];
+        for (int i = 0; i < TM; ++i) {
+            if constexpr (AT && TRP) af[i] = lfrag_tr<BM * 2>(reinterpret_cast<const char*>(a_s) + troff_a[i], 16 * q);
+            else af[i] = a_s[roff_a[(i & 1) ? (q ^ 2) : q] + i * 32 * CHUNKS];
+        }
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bf[j] = b_s[roff_b[(j & 1) ? (q ^ 2) : q] + j * 32 * CHUNKS];
+        for (int j = 0; j < TN; ++j) {
+            if constexpr (BT && TRP) bf[j] = lfrag_tr<BN * 2>(reinterpret_cast<const char*>(b_s) + troff_b[j], 16 * q);
+            else bf[j] = b_s[roff_b[(j & 1) ? (q ^ 2) : q] + j * 32 * CHUNKS];
+        }
     };
 
     const int nslab = it_end - it_begin;
@@ -435,7 +470,7 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
                 for (int j = 0; j < TN; ++j) mma<TI>(acc[i][j], af[q % NF][i], bf[q % NF][j]);
             if (RS && do_rs && it < ntiles[0]) {
 #pragma unroll
-                for (int i = 0; i < NRS; ++i) mma<TI>(rs[i], af[q % NF][i], ones);
+                for (int i = 0; i < NRS; ++i) rs[i] = add_row(rs[i], af[q % NF][i]);
             }
         }
         if (steady || it + 1 < it_end) sstore(buf ^ 1, ra_nxt, rb_nxt);
@@ -452,15 +487,14 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
             if (it + u < it_end) step(it + u, false, ra[u], rb[u], ra[(u + 1) % D], rb[(u + 1) % D]);
     }
 
-    if (RS && do_rs && (lane & 31) == 0) {
+    if (RS && do_rs) {
         float* out = P.splits > 1 ? P.rs_partial + ((long long)z * P.splits + split) * P.M : P.rowsum + z * P.sRowsum;
 #pragma unroll
-        for (int i = 0; i < NRS; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = row0 + wm * (32 * TM) + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (row < P.M) out[row] = rs[i][e];
-            }
+        for (int i = 0; i < NRS; ++i) {
+            const float total = rs[i] + __shfl_xor(rs[i], 32);          // the other half of every sub-step
+            const int row = row0 + wm * (32 * TM) + i * 32 + (lane & 31);
+            if (lane < 32 && row < P.M) out[row] = total;
+        }
     }
 
     // Epilogue: accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32.
@@ -576,6 +610,7 @@ int fast_flags(const void* p, long long ld, long long stride, int batch, bool ro
     } else {
         const long long w = 4 * es;                       // four consecutive rows per load
         if (aligned(p, w) && (ld * es) % w == 0 && (stride * es) % w == 0) f |= 1;
+        if (es == 2 && aligned(p, 16) && (ld * es) % 16 == 0 && (stride * es) % 16 == 0) f |= 4;   // eight rows per load
     }
     return f;
 }
@@ -634,6 +669,7 @@ bool can_run_fast(const GemmDesc& d, const Params& P, int tile) {
     for (int s = 0; s < d.nseg; ++s) {
         if (d.seg[s].K % bk) return false;
         if (!(P.A[s].fast & 1) || !(P.B[s].fast & 1)) return false;
+        if (sizeof(TI) == 2 && ((d.atrans && !(P.A[s].fast & 4)) || (d.btrans && !(P.B[s].fast & 4)))) return false;
         if (d.seg[s].lda != d.seg[0].lda || d.seg[s].ldb != d.seg[0].ldb) return false;
         if (d.seg[s].lda * (long long)sizeof(TI) * 64 > 0x3FFFFFFF || d.seg[s].ldb * (long long)sizeof(TI) * 64 > 0x3FFFFFFF) return false;
     }
@@ -708,7 +744,10 @@ GemmPlan plan_gemm(const GemmDesc& d) {
             while (s > 1 && slabs / s < min_slabs) --s;
             return s < 1 ? 1 : s;
         };
-        const int s1 = parts(256, 8), s2 = parts(512, 64);
+#ifndef GEMM_SPLIT2_MIN
+#define GEMM_SPLIT2_MIN 64
+#endif
+        const int s1 = parts(256, 8), s2 = parts(512, GEMM_SPLIT2_MIN);
         const int s = s1 > s2 ? s1 : s2;
         const size_t need = (size_t)s * batch * ((size_t)d.M * d.N + d.M) * sizeof(float);
         if (s > 1 && need <= d.partial_bytes) {
