@@ -257,23 +257,31 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             const bool ok = FULL || b0 + rb + re(e) < B;
 #pragma unroll
             for (int g = 0; g < 4; ++g) ax[e][g] = ok ? axb[o8b + (unsigned)((re(e) * 8 + g) * H)] : 0.0f;
-            cp[e] = (ok && n > 0) ? cpb[o2b + (unsigned)(re(e) * 2 * H)] : 0.0f;
+            cp[e] = (ok && n > 0 && ntl > 1) ? cpb[o2b + (unsigned)(re(e) * 2 * H)] : 0.0f;   // (one tile: c stays in registers)
         }
     };
 
     const int nitems = T * ntl;
-    float ax[EPT][4], cp[EPT];
-    issue_inputs(0, ax, cp);
+    // Two sets of input registers used in turn: an item computes from one while the next item's loads land
+    // in the other, so nothing is copied (a copy would have to wait for loads issued a moment before).
+    float ax0[EPT][4], cp0[EPT], ax1[EPT][4], cp1[EPT];
+    issue_inputs(0, ax0, cp0);
+    // Waited for here, once: the compiler places its waits for the worst path into the loop, and with these
+    // loads still in flight on the way in, that path would make every item wait for its freshly issued loads.
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0) (expcnt and lgkmcnt left alone)
+    float ccarry[EPT];                                   // one tile per workgroup: its cell state of the frame before
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) ccarry[e] = 0.0f;
     // With several batch tiles per workgroup the next item's h was written a whole frame ago: its
     // chunks are loaded while this item computes (checked for the sentinel like any other load).
     uint4 apre[MULTI ? KSTEPS : 1];
     bool have_pre = false;
-    for (int item = 0; item < nitems; ++item) {
+    auto do_item = [&](const int item, const float (&ax)[EPT][4], const float (&cpl)[EPT], float (&axn)[EPT][4],
+                       float (&cpn)[EPT]) __attribute__((always_inline)) {
         const int n = item / ntl, i = item - n * ntl;
         const int t = d ? T - 1 - n : n;
         const int tp = d ? T - n : n - 1;
         const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
-        float axn[EPT][4], cpn[EPT];
         float sum[EPT][4];
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
@@ -303,14 +311,12 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                     asm volatile("" ::: "memory");
                     load_chunks_cached<KSTEPS>(afrag, hp, valid);
                 }
-                if (item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
                 ensure_written<KSTEPS>(afrag, hp, valid, gu, a.abort_word, a.limit_ticks);
             } else {
                 wait_counter(cnt + i, (unsigned)(NU * n), a.abort_word, a.limit_ticks);
 #pragma unroll
                 for (int q = 0; q < KSTEPS; ++q)
                     afrag[q] = valid ? *reinterpret_cast<const uint4*>(hp + q * XPAIR) : make_uint4(0, 0, 0, 0);
-                if (item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
             }
             f32x16_t acc[4];
 #pragma unroll
@@ -358,9 +364,16 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                         const float4 v = part[w2][g][e4];
                         sum[4 * e4][g] += v.x; sum[4 * e4 + 1][g] += v.y; sum[4 * e4 + 2][g] += v.z; sum[4 * e4 + 3][g] += v.w;
                     }
-        } else if (item + 1 < nitems) {
-            issue_inputs(item + 1, axn, cpn);
         }
+        // The next item's inputs come from HBM, and a CU's vector memory pipeline returns data in order:
+        // issued any earlier, they would sit in front of another wavefront's loads of the exchanged h and
+        // add their latency to the frame-to-frame path.  Here every wavefront of the workgroup has its h (the
+        // barrier above).  (One place for both branches above, so that the loads land where the next item
+        // reads them and nothing waits for them on the way.)
+        float cp[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) cp[e] = (ntl == 1) ? ccarry[e] : cpl[e];
+        if (item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
         // cell arithmetic; h goes out first because it is all the other workgroups wait for
         float gi[EPT], gf[EPT], gg[EPT], go[EPT], cn[EPT], hn[EPT];
         bf16_t* hxb = a.hx + ((size_t)(t * 2 + d) * NT + (b0 >> 5)) * XH;
@@ -393,12 +406,25 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                 *reinterpret_cast<uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) = make_uint2(pack_bf2(gi[e], gf[e]), pack_bf2(gg[e], go[e]));
             }
         }
-        // next item's inputs; with one tile per workgroup its previous cell state is the one just computed
+        // with one tile per workgroup the next item's previous cell state is the one just computed
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) {
+        for (int e = 0; e < EPT; ++e) ccarry[e] = cn[e];
+    };
+    if constexpr (KW <= 128) {
+        for (int item = 0; item < nitems; item += 2) {
+            do_item(item, ax0, cp0, ax1, cp1);
+            if (item + 1 < nitems) do_item(item + 1, ax1, cp1, ax0, cp0);
+        }
+    } else {
+        // (the widest slice of U_h leaves no room for the loop body twice: one body, and a copy at its end)
+        for (int item = 0; item < nitems; ++item) {
+            do_item(item, ax0, cp0, ax1, cp1);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) ax[e][g] = axn[e][g];
-            cp[e] = (ntl == 1) ? cn[e] : cpn[e];
+            for (int e = 0; e < EPT; ++e) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) ax0[e][g] = ax1[e][g];
+                cp0[e] = cp1[e];
+            }
         }
     }
 }
@@ -466,23 +492,26 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
             in.c[e] = ok ? cb[o2] : 0.0f;
             in.cp[e] = (ok && n > 0) ? cpb[o2] : 0.0f;
             in.dy[e] = ok ? dyb[o2] : (bf16_t)0;
-            in.dcr[e] = (ok && n < T - 1) ? dcb[o1b + (unsigned)(re(e) * H)] : 0.0f;
+            in.dcr[e] = (ok && n < T - 1 && ntl > 1) ? dcb[o1b + (unsigned)(re(e) * H)] : 0.0f;   // (one tile: carried in registers)
         }
     };
 
     static_assert(EPT <= 8, "two sets of inputs (this item's and the next one's) must fit in registers");
     const int nitems = T * ntl;
-    Inputs cur;
-    issue_inputs(0, cur);
+    Inputs in0, in1;                                     // two sets used in turn, as in the forward kernel
+    issue_inputs(0, in0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): see the forward kernel
+    float dccarry[EPT];                                  // one tile per workgroup: its dE/dc of the frame visited before
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) dccarry[e] = 0.0f;
     uint4 apre[MULTI ? 8 : 1];                           // first slab of the next item, loaded ahead (several tiles only)
     bool have_pre = false;
-    for (int item = 0; item < nitems; ++item) {
+    auto do_item = [&](const int item, const Inputs& cur, Inputs& nxt) __attribute__((always_inline)) {
         const int ni = item / ntl, i = item - ni * ntl;
         const int n = T - 1 - ni;
         const int t = d ? T - 1 - n : n;
         const int tn = d ? T - 2 - n : n + 1;            // frame visited after t (its da feeds dh)
         const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
-        Inputs nxt;
         float dh[EPT];
 #pragma unroll
         for (int e = 0; e < EPT; ++e) dh[e] = 0.0f;
@@ -517,7 +546,6 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 for (int sl = 0; sl < KSTEPS / 8; ++sl) {
                     if (sl + 1 < KSTEPS / 8) load_chunks_cached<8>(afrag[(sl + 1) & 1], ap + (sl + 1) * 8 * XPAIR, valid);
                     else {
-                        if (item + 1 < nitems) issue_inputs(item + 1, nxt);
                         have_pre = false;
                         if constexpr (MULTI && KW == 128) if (ntl >= 2 && item + 1 < nitems) {
                             const int ni2 = (item + 1) / ntl, i2 = (item + 1) - ni2 * ntl;
@@ -544,7 +572,6 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
 #pragma unroll
                     for (int q = 0; q < 8; ++q)
                         afrag[q] = valid ? *reinterpret_cast<const uint4*>(ap + (q0 + q) * XPAIR) : make_uint4(0, 0, 0, 0);
-                    if (q0 + 8 >= KSTEPS && item + 1 < nitems) issue_inputs(item + 1, nxt);
 #pragma unroll
                     for (int q = 0; q < 8; ++q) acc = mfma_bf16(afrag[q], bfrag[q0 + q], acc);
                 }
@@ -568,9 +595,12 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                     const float4 v = part[w2][e4];
                     dh[4 * e4] += v.x; dh[4 * e4 + 1] += v.y; dh[4 * e4 + 2] += v.z; dh[4 * e4 + 3] += v.w;
                 }
-        } else if (item + 1 < nitems) {
-            issue_inputs(item + 1, nxt);
         }
+        // (the next item's inputs only now, as in the forward kernel: not in front of anyone's exchange loads)
+        float dcr[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) dcr[e] = (ntl == 1) ? dccarry[e] : cur.dcr[e];
+        if (item + 1 < nitems) issue_inputs(item + 1, nxt);
         float dcf[EPT];
         unsigned dav[EPT][2];                             // (i, f) and (g, o) as bf16 pairs: kept for the row-major copy below
         bf16_t* dxb = a.dax + ((size_t)(t * 2 + d) * NT + (b0 >> 5)) * XA;
@@ -580,7 +610,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
             const float gg = bf2f((bf16_t)(cur.g[e].y & 0xFFFFu)), go = bf2f((bf16_t)(cur.g[e].y >> 16));
             const float dht = dh[e] + bf2f(cur.dy[e]);
             const float tc = fast_tanh(cur.c[e]);
-            const float dc = dht * go * (1.0f - tc * tc) + cur.dcr[e];
+            const float dc = dht * go * (1.0f - tc * tc) + dcr[e];
             const float da_o = dht * tc * go * (1.0f - go);
             const float da_i = dc * gg * gi * (1.0f - gi);
             const float da_f = dc * cur.cp[e] * gf * (1.0f - gf);
@@ -611,10 +641,18 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 for (int g = 0; g < 4; ++g) dab[o8b + (unsigned)((re(e) * 8 + g) * H)] = (bf16_t)(dav[e][g >> 1] >> (16 * (g & 1)));
             }
         // next item's inputs; with one tile per workgroup its carried dE/dc is the one just computed
-        cur = nxt;
-        if (ntl == 1) {
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) cur.dcr[e] = dcf[e];
+        for (int e = 0; e < EPT; ++e) dccarry[e] = dcf[e];
+    };
+    if constexpr (KW <= 128) {
+        for (int item = 0; item < nitems; item += 2) {
+            do_item(item, in0, in1);
+            if (item + 1 < nitems) do_item(item + 1, in1, in0);
+        }
+    } else {
+        for (int item = 0; item < nitems; ++item) {
+            do_item(item, in0, in1);
+            in0 = in1;
         }
     }
 }
