@@ -307,9 +307,23 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                     }
                 }
                 if (!got) {
-                    gu = wait_probe(probe, lane < KW / 32, a.abort_word, a.limit_ticks);
-                    asm volatile("" ::: "memory");
-                    load_chunks_cached<KSTEPS>(afrag, hp, valid);
+                    // Straight for the data: this wavefront's loads queue behind its own stores of the item
+                    // before, whose acknowledgements take about as long as the other workgroups' h takes to
+                    // arrive, so the first look nearly always finds everything.  If not: the cheap probe, then
+                    // cache-bypassing loads (the first ones may have left lines with sentinels in the L1).
+                    // (The widest slice has no registers for two attempts: probe first, then the data.)
+                    if constexpr (KW <= 128) {
+                        load_chunks_cached<KSTEPS>(afrag, hp, valid);
+                        if (!all_written<KSTEPS>(afrag)) {
+                            gu = wait_probe(probe, lane < KW / 32, a.abort_word, a.limit_ticks);
+                            asm volatile("" ::: "memory");
+                            load_chunks<KSTEPS>(afrag, hp, valid);
+                        }
+                    } else {
+                        gu = wait_probe(probe, lane < KW / 32, a.abort_word, a.limit_ticks);
+                        asm volatile("" ::: "memory");
+                        load_chunks_cached<KSTEPS>(afrag, hp, valid);
+                    }
                 }
                 ensure_written<KSTEPS>(afrag, hp, valid, gu, a.abort_word, a.limit_ticks);
             } else {
@@ -365,15 +379,13 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                         sum[4 * e4][g] += v.x; sum[4 * e4 + 1][g] += v.y; sum[4 * e4 + 2][g] += v.z; sum[4 * e4 + 3][g] += v.w;
                     }
         }
-        // The next item's inputs come from HBM, and a CU's vector memory pipeline returns data in order:
-        // issued any earlier, they would sit in front of another wavefront's loads of the exchanged h and
-        // add their latency to the frame-to-frame path.  Here every wavefront of the workgroup has its h (the
-        // barrier above).  (One place for both branches above, so that the loads land where the next item
-        // reads them and nothing waits for them on the way.)
+        // (The next item's inputs come from HBM, and a CU's vector memory pipeline returns data in order: issued
+        // before the barrier above they would sit in front of another wavefront's loads of the exchanged h and
+        // add their latency to the frame-to-frame path.  They are issued below, once h has gone out.)
         float cp[EPT];
 #pragma unroll
         for (int e = 0; e < EPT; ++e) cp[e] = (ntl == 1) ? ccarry[e] : cpl[e];
-        if (item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
+        if (KW > 128 && item + 1 < nitems) issue_inputs(item + 1, axn, cpn);   // (widest slice: registers are short later on)
         // cell arithmetic; h goes out first because it is all the other workgroups wait for
         float gi[EPT], gf[EPT], gg[EPT], go[EPT], cn[EPT], hn[EPT];
         bf16_t* hxb = a.hx + ((size_t)(t * 2 + d) * NT + (b0 >> 5)) * XH;
@@ -390,6 +402,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                 if (SENTINEL) st_coh_bf16(xp, hn[e]); else *xp = f2bf(hn[e]);
             }
         }
+        if (KW <= 128 && item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
         if (SENTINEL) lds_barrier();                     // frees the LDS buffer for the next item
         else signal_counter(cnt + i);                    // barrier inside: same role
         // row-major outputs (h for the next layer, c and the gates for the backward pass): off the
@@ -538,9 +551,13 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                     }
                 }
                 if (!got) {
-                    gu = wait_probe(probe, lane < 4 * KW / 32, a.abort_word, a.limit_ticks);
-                    asm volatile("" ::: "memory");
+                    // (straight for the data, the probe only if the first look fails: see the forward kernel)
                     load_chunks_cached<8>(afrag[0], ap, valid);
+                    if (!all_written<8>(afrag[0])) {
+                        gu = wait_probe(probe, lane < 4 * KW / 32, a.abort_word, a.limit_ticks);
+                        asm volatile("" ::: "memory");
+                        load_chunks<8>(afrag[0], ap, valid);
+                    }
                 }
 #pragma unroll
                 for (int sl = 0; sl < KSTEPS / 8; ++sl) {
@@ -596,11 +613,10 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                     dh[4 * e4] += v.x; dh[4 * e4 + 1] += v.y; dh[4 * e4 + 2] += v.z; dh[4 * e4 + 3] += v.w;
                 }
         }
-        // (the next item's inputs only now, as in the forward kernel: not in front of anyone's exchange loads)
         float dcr[EPT];
 #pragma unroll
         for (int e = 0; e < EPT; ++e) dcr[e] = (ntl == 1) ? dccarry[e] : cur.dcr[e];
-        if (item + 1 < nitems) issue_inputs(item + 1, nxt);
+        if (KW > 128 && item + 1 < nitems) issue_inputs(item + 1, nxt);
         float dcf[EPT];
         unsigned dav[EPT][2];                             // (i, f) and (g, o) as bf16 pairs: kept for the row-major copy below
         bf16_t* dxb = a.dax + ((size_t)(t * 2 + d) * NT + (b0 >> 5)) * XA;
@@ -628,6 +644,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
                 }
             }
         }
+        if (KW <= 128 && item + 1 < nitems) issue_inputs(item + 1, nxt);
         if (SENTINEL) lds_barrier();
         else signal_counter(cnt + i);
         // row-major dE/da for the weight- and input-gradient products, and the carried dE/dc
