@@ -473,7 +473,10 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
                 ta.src[2 * l + d] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[d][l], e));
         ta.dst = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wUHT);
         ta.count = 2 * ctx->L;
-        RUN(PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, st));
+        // (on the stream of the weight-gradient products when there is one: the first recurrence waits for that
+        // stream's sentinel fill anyway, and the bottleneck's input gradient runs on `st` meanwhile)
+        if (ov && sentinel) RUN_ON(ws, PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, ws));
+        else RUN(PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, st));
     }
     // In sentinel mode every layer's exchange copy of dE/da starts as "not written yet": one fill,
     // on the stream of the weight-gradient products so that it runs beside the products at the top.
