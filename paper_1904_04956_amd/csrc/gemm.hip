@@ -732,6 +732,18 @@ GemmPlan plan_gemm(const GemmDesc& d) {
     int ktot = 0;
     for (int s = 0; s < d.nseg; ++s) ktot += d.seg[s].K;
     if (t256 >= 512 && !d.rowsum && ktot >= 512) { p.big_tile = true; return p; }
+    // A handful of large tiles and a very long contraction (the softmax layer's input gradient): the large
+    // tile, which moves half the operand bytes per flop, split along K over up to one workgroup per CU, if
+    // every part keeps at least 24 slabs and the parts fill three quarters of the CUs.
+    if (d.nseg == 1 && !d.add && !d.rowsum && d.partial && d.in_type == DT_BF16 && t256 <= 64 &&
+        d.M % 256 == 0 && d.N % 256 == 0 && d.seg[0].K % 64 == 0) {
+        const int slabs = d.seg[0].K / 64;
+        int s = (int)(256 / t256);
+        if (s > 16) s = 16;
+        while (s > 1 && slabs / s < 24) --s;
+        const size_t need = (size_t)s * batch * ((size_t)d.M * d.N + d.M) * sizeof(float);
+        if (s > 1 && t256 * s >= 192 && need <= d.partial_bytes) { p.big_tile = true; p.splits = s; p.partial_bytes = need; return p; }
+    }
     // Few output tiles and a long contraction: split K.  Up to one workgroup per CU whenever each part
     // keeps at least 8 slabs; up to two per CU (the number that fit) when each part keeps at least 64,
     // so that the float partial tiles and the reduction stay small next to the product itself.
