@@ -59,6 +59,8 @@ struct blstm_ctx {
     // workspace (byte offsets)
     std::vector<size_t> wY, wG, wC;
     size_t wAX, wPRE, wDA[2], wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, wPART2, wHX, wDAX, hx_bytes, dax_bytes, part_bytes, part2_bytes, ws_bytes;
+    int Dp;                   // 0, or the first layer's input width rounded up to whole tiles (padded copies of x and W_x)
+    size_t wXP, wWP;
     int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
@@ -201,6 +203,15 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     c->wDC = w;      w += up256(2 * B * H * 4);
     c->wLOGITS = w;  w += up256(M * (size_t)c->V * e);
     c->wROWLOSS = w; w += up256(M * 4);
+    // A feature width that is not a whole number of tiles (the paper's 260) would put the first layer's two
+    // products on the guarded kernel, three times slower: zero-padded bf16 copies of x and of W_x of layer 0
+    // (a few MB) keep them on the unguarded one.
+    c->Dp = 0; c->wXP = w; c->wWP = w;
+    if (c->st == DT_BF16 && c->D % 128 != 0 && c->M % 128 == 0 && (4 * c->H) % 128 == 0) {
+        c->Dp = (c->D + 127) / 128 * 128;
+        c->wXP = w; w += up256(M * (size_t)c->Dp * 2);
+        c->wWP = w; w += up256((size_t)2 * 4 * H * c->Dp * 2);
+    }
     // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
     c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false;
     c->fwd_persistent.assign(c->L, 0);
@@ -321,6 +332,19 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
             d.batch = 2; d.M = M; d.N = 4 * H;
             d.seg[0] = GemmSeg{Xin, at(theta, ctx->off_wx[0][l], e), Din, Din, 0,
                                (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]), Din};
+            if (l == 0 && ctx->Dp > 0) {                 // zero-padded copies: K = Dp, whole slabs
+                PadColsArgs pa{};
+                unsigned short* XP = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wXP);
+                unsigned short* WP = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wWP);
+                pa.src[0] = static_cast<const unsigned short*>(x); pa.dst[0] = XP; pa.ld[0] = Din; pa.rows[0] = M;
+                for (int dd = 0; dd < 2; ++dd) {
+                    pa.src[1 + dd] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_wx[dd][0], e));
+                    pa.dst[1 + dd] = WP + (size_t)dd * 4 * H * ctx->Dp; pa.ld[1 + dd] = Din; pa.rows[1 + dd] = 4 * H;
+                }
+                pa.count = 3; pa.cols = Din; pa.cols_p = ctx->Dp;
+                RUN(PC_MISC, "padded copies of x and W_x", launch_pad_cols(pa, st));
+                d.seg[0] = GemmSeg{XP, WP, ctx->Dp, ctx->Dp, 0, (long long)4 * H * ctx->Dp, ctx->Dp};
+            }
             d.C = AX; d.ldc = 8 * H; d.sC = 4 * H;
             d.bias = at(theta, ctx->off_b[0][l], e); d.sBias = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);
             RUN(PC_GEMM_INPUT, "input projection", launch_gemm(d, st));
@@ -580,6 +604,10 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             GemmDesc d = wgrad_desc(DT_F32);
             d.batch = 2; d.M = 4 * H; d.N = Din; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{DA, Xin, 8 * H, Din, 4 * H, 0, M};
+            if (l == 0 && ctx->Dp > 0) {                 // the forward pass's padded x: whole tiles of columns, N of them stored
+                d.seg[0] = GemmSeg{DA, ctx->ws + ctx->wXP, 8 * H, ctx->Dp, 4 * H, 0, M};
+                d.Npad = ctx->Dp;
+            }
             d.C = grad + ctx->off_wx[0][l]; d.ldc = Din; d.sC = (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]);
             d.rowsum = grad + ctx->off_b[0][l];        // db = sum over frames of da
             d.sRowsum = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);

@@ -665,7 +665,7 @@ hipError_t launch_form(const GemmDesc& d, const Params& P, bool fast, bool deep,
 template <typename TI>
 bool can_run_fast(const GemmDesc& d, const Params& P, int tile) {
     const int bk = CHUNKS * Vec<TI>::N;
-    if (d.M % tile || d.N % tile) return false;
+    if (d.M % tile || (d.Npad > 0 ? d.Npad : d.N) % tile) return false;
     for (int s = 0; s < d.nseg; ++s) {
         if (d.seg[s].K % bk) return false;
         if (!(P.A[s].fast & 1) || !(P.B[s].fast & 1)) return false;
@@ -699,12 +699,13 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     GemmPlan plan = plan_gemm(d);
     if (plan.big_tile && !can_run_fast<TI>(d, P, 256)) plan.big_tile = false;   // the large tile has no guarded form
     const int tile = plan.big_tile ? 256 : 128;
-    P.ntm = (d.M + tile - 1) / tile; P.ntn = (d.N + tile - 1) / tile;
+    const bool fast = can_run_fast<TI>(d, P, tile);
+    if (fast && d.Npad > 0) P.c_vec = 0;                 // whole tiles are computed, the stores stop at column N
+    P.ntm = (d.M + tile - 1) / tile; P.ntn = ((fast && d.Npad > 0 ? d.Npad : d.N) + tile - 1) / tile;
     P.splits = plan.splits;
     P.partial = plan.splits > 1 ? d.partial : nullptr;
     P.rs_partial = plan.splits > 1 ? d.partial + (size_t)plan.splits * batch * d.M * d.N : nullptr;
     dim3 grid((unsigned)(P.ntm * P.ntn), (unsigned)plan.splits, (unsigned)batch);
-    const bool fast = can_run_fast<TI>(d, P, tile);
     hipError_t e;
     if (plan.splits > 1) {
         // partial tiles are float whatever the output type
@@ -725,8 +726,9 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
 GemmPlan plan_gemm(const GemmDesc& d) {
     GemmPlan p{false, false, 1, 0};
     const int batch = d.batch > 0 ? d.batch : 1;
-    const long long t256 = (long long)((d.M + 255) / 256) * ((d.N + 255) / 256) * batch;
-    const long long t128 = (long long)((d.M + 127) / 128) * ((d.N + 127) / 128) * batch;
+    const int Ne = d.Npad > 0 ? d.Npad : d.N;             // (the caller sets Npad only where the unguarded kernel applies)
+    const long long t256 = (long long)((d.M + 255) / 256) * ((Ne + 255) / 256) * batch;
+    const long long t128 = (long long)((d.M + 127) / 128) * ((Ne + 127) / 128) * batch;
     // the large tile has one workgroup per CU, so its prologue and epilogue are exposed: it pays only
     // when the contraction is long enough to amortise them
     int ktot = 0;

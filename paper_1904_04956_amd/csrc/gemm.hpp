@@ -31,6 +31,8 @@ struct GemmDesc {
     float* partial;           // scratch for split-K partial tiles (float), or null: never split
     size_t partial_bytes;
     int M, N, batch;
+    int Npad;                 // 0, or a multiple of the tile width >= N up to which B(n, .) may be read (it holds zeros or
+                              // anything there): the product runs on whole tiles, C keeps its N columns
     bool atrans, btrans;
     DType in_type, out_type;  // in_type is the element type of A and B
 };

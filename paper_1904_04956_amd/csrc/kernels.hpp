@@ -75,6 +75,16 @@ struct TransposeUhArgs {
 };
 hipError_t launch_transpose_uh(const TransposeUhArgs& a, int H, hipStream_t st);
 hipError_t launch_fill_u32(unsigned* p, int n, unsigned v, hipStream_t st);
+// Copies up to three row-major 16-bit matrices [rows][cols] (leading dimension ld) into [rows][cols_p] ones
+// with zeros in columns cols .. cols_p - 1 (cols_p a multiple of 8, dst 16-byte aligned).
+struct PadColsArgs {
+    const unsigned short* src[3];
+    unsigned short* dst[3];
+    long long ld[3];
+    int rows[3];
+    int count, cols, cols_p;
+};
+hipError_t launch_pad_cols(const PadColsArgs& a, hipStream_t st);
 // Fills bytes/16 16-byte words with the 32-bit pattern v.
 hipError_t launch_fill_bytes16(void* p, size_t bytes, unsigned v, hipStream_t st);
 

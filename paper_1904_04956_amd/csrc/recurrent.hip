@@ -686,6 +686,32 @@ __global__ __launch_bounds__(256) void transpose_uh_kernel(TransposeUhArgs a, in
     for (int rr = ty; rr < 32; rr += 8) dst[(size_t)(c0 + rr) * 4 * H + r0 + tx] = tile[tx][rr];
 }
 
+// dst[r][0..cols_p) = src[r][0..cols) followed by zeros: one thread per 8-column chunk, grid-stride.
+__global__ __launch_bounds__(256) void pad_cols_kernel(PadColsArgs a) {
+    const int k = blockIdx.y;
+    const unsigned short* src = a.src[k];
+    unsigned short* dst = a.dst[k];
+    const long long ld = a.ld[k];
+    const int cpr = a.cols_p >> 3;
+    const long long n = (long long)a.rows[k] * cpr;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        const long long r = i / cpr;
+        const int c = (int)(i - r * cpr) * 8;
+        uint4 out;
+        const unsigned short* p = src + r * ld + c;
+        if (c + 8 <= a.cols && (reinterpret_cast<uintptr_t>(p) & 7) == 0) {      // whole chunk, 8-byte aligned: two loads
+            const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + 4);
+            out = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        } else {
+            unsigned short v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = (c + e < a.cols) ? p[e] : (unsigned short)0;
+            out = make_uint4(v[0] | ((unsigned)v[1] << 16), v[2] | ((unsigned)v[3] << 16), v[4] | ((unsigned)v[5] << 16), v[6] | ((unsigned)v[7] << 16));
+        }
+        *reinterpret_cast<uint4*>(dst + r * a.cols_p + c) = out;
+    }
+}
+
 // p[0..n) = v for 16-byte words, grid-stride.
 __global__ __launch_bounds__(256) void fill_u128_kernel(uint4* p, size_t n, unsigned v) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -777,6 +803,17 @@ hipError_t launch_fill_bytes16(void* p, size_t bytes, unsigned v, hipStream_t st
     size_t blocks = (n + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(fill_u128_kernel, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<uint4*>(p), n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_cols(const PadColsArgs& a, hipStream_t st) {
+    if (a.count <= 0) return hipSuccess;
+    long long most = 0;
+    for (int k = 0; k < a.count; ++k) { const long long n = (long long)a.rows[k] * (a.cols_p / 8); if (n > most) most = n; }
+    if (most == 0) return hipSuccess;
+    long long blocks = (most + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(pad_cols_kernel, dim3((unsigned)blocks, (unsigned)a.count), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
