@@ -134,6 +134,7 @@ def test_loss_scale_argument_fp32():
     dict(T=3, B=5, D=7, H=6, L=1, P=0, V=11),               # odd leading dimensions: scalar load paths
     dict(T=4, B=32, D=37, H=32, L=2, P=0, V=50),            # M = 4H = 128, odd D: zero-padded copies of x and W_x, unaligned rows
     dict(T=8, B=32, D=200, H=64, L=1, P=16, V=60),          # ... D = 200 padded to 256: two tile columns of dW_x, the second ragged
+    dict(T=21, B=128, D=37, H=32, L=1, P=0, V=50),          # ... with a contraction long enough for dW_x to be split along K
 ])
 def test_shapes_bf16(dims):
     check_step(dims, 1, seed=78, theta_scale=2.0)
