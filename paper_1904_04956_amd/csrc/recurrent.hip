@@ -75,6 +75,15 @@ __device__ __forceinline__ bf16_t coh_bf16(float v) {
 __device__ __forceinline__ void st_coh_bf16(bf16_t* p, float v) {
     __hip_atomic_store(p, coh_bf16(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_coh_8B(bf16_t* p, const uint2& v) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), (unsigned long long)v.x | ((unsigned long long)v.y << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coh_16B(bf16_t* p, const uint4& v) {
+    unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
+    __hip_atomic_store(q, (unsigned long long)v.x | ((unsigned long long)v.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(q + 1, (unsigned long long)v.z | ((unsigned long long)v.w << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ uint4 ld_coh_16B(const bf16_t* p) {
     const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
     const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -239,7 +248,6 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     const int NT = (B + 31) / 32;                        // 32-row tiles of the batch
     constexpr int XH = H / 16 * XPAIR;                   // exchange elements per (frame, direction, tile)
     const unsigned ohp = (unsigned)(wave * (KW / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
-    const unsigned oxs = xoff(j, rb);                    // where this thread's h of row rb goes
 
     // Per-item inputs that do not depend on the exchange (a_x of the frame, previous cell state) are
     // loaded one item ahead, so that their HBM latency never sits on the frame-to-frame path.
@@ -397,10 +405,27 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             go[e] = fast_sigmoid(ax[e][3] + sum[e][3]);
             cn[e] = gf[e] * cp[e] + gi[e] * gg[e];
             hn[e] = go[e] * fast_tanh(cn[e]);
-            if (FULL || b0 + rb + re(e) < B) {
-                bf16_t* xp = hxb + (oxs + (unsigned)(re(e) * 8));
-                if (SENTINEL) st_coh_bf16(xp, hn[e]); else *xp = f2bf(hn[e]);
-            }
+        }
+        // A lane holds four rows of one unit; both copies of h want the units of a row side by side.  Regrouped
+        // through LDS inside the wavefront (as dE/da in the backward kernel), every lane stores four units of one
+        // row: one 8-byte store per copy instead of four 2-byte ones.
+        static_assert(EPT == 4, "the regrouping below is written for four rows per lane");
+        unsigned* xs = reinterpret_cast<unsigned*>(lds) + NW * 4 * 4 * 64 * 4 + wave * 128;
+        xs[(lh * 2 + 0) * 32 + l32] = (unsigned)coh_bf16(hn[0]) | ((unsigned)coh_bf16(hn[1]) << 16);
+        xs[(lh * 2 + 1) * 32 + l32] = (unsigned)coh_bf16(hn[2]) | ((unsigned)coh_bf16(hn[3]) << 16);
+        const int xh = lane & 1, xk = (lane >> 1) & 3, xr = (lane >> 3) & 3, xl = lane >> 5;
+        uint2 hq;                                         // units 8 xk + 4 xh .. + 3 of row xrow
+        {
+            const uint4 w = *reinterpret_cast<const uint4*>(xs + (xl * 2 + (xr >> 1)) * 32 + 8 * xk + 4 * xh);
+            const unsigned sel = (xr & 1) ? 0x07060302u : 0x05040100u;
+            hq = make_uint2(__builtin_amdgcn_perm(w.y, w.x, sel), __builtin_amdgcn_perm(w.w, w.z, sel));
+        }
+        const int xrow = 2 * EPT * wave + 4 * xl + xr;    // row of the tile
+        const bool xok = FULL || b0 + xrow < B;
+        const unsigned xcol = (unsigned)(u * 32 + 8 * xk + 4 * xh);
+        if (xok) {
+            bf16_t* xp = hxb + ((xcol >> 3) * 256u + (unsigned)xrow * 8u + (xcol & 7u));
+            if (SENTINEL) st_coh_8B(xp, hq); else *reinterpret_cast<uint2*>(xp) = hq;
         }
         if (KW <= 128 && item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
         if (SENTINEL) lds_barrier();                     // frees the LDS buffer for the next item
@@ -414,11 +439,11 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         for (int e = 0; e < EPT; ++e) {
             if (FULL || b0 + rb + re(e) < B) {
                 cb[o2b + (unsigned)(re(e) * 2 * H)] = cn[e];
-                yb[o2b + (unsigned)(re(e) * 2 * H)] = f2bf(hn[e]);
                 // the four gate activations of a unit are one 8-byte word: [frame row][direction][unit][gate]
                 *reinterpret_cast<uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) = make_uint2(pack_bf2(gi[e], gf[e]), pack_bf2(gg[e], go[e]));
             }
         }
+        if (xok) *reinterpret_cast<uint2*>(yb + ((unsigned)xrow * (unsigned)(2 * H) + (unsigned)(d * H) + xcol)) = hq;
         // with one tile per workgroup the next item's previous cell state is the one just computed
 #pragma unroll
         for (int e = 0; e < EPT; ++e) ccarry[e] = cn[e];
@@ -476,12 +501,10 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     auto re = [](int e) { return 8 * (e >> 2) + (e & 3); };
     const unsigned o1b = (unsigned)(rb * H + j);                 // into [.][H] (carried dE/dc),
     const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // [.][2H] (c, dy)
-    const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // the row-major [.][8H] tensor (dE/da)
     const unsigned ogb = (unsigned)(rb * 8 * H + (d * H + j) * 4); // and the saved gates, [.][2][H][4]
     const int NT = (B + 31) / 32;
     constexpr int XA = 4 * H / 16 * XPAIR;               // exchange elements per (frame, direction, tile)
     const unsigned oap = (unsigned)(wave * (KWB / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
-    const unsigned oxs = xoff(j, rb);                    // where this thread's dE/da of gate 0, row rb goes
 
     // Saved activations of an item, loaded one item ahead (raw bf16 for the gates and dy).
     struct Inputs { uint2 g[EPT]; bf16_t dy[EPT]; float c[EPT], cp[EPT], dcr[EPT]; };   // g: (i, f), (g, o) as bf16 pairs
@@ -502,7 +525,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
             const bool ok = FULL || b0 + rb + re(e) < B;
             const unsigned o2 = o2b + (unsigned)(re(e) * 2 * H);
             in.g[e] = ok ? *reinterpret_cast<const uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) : make_uint2(0u, 0u);
-            in.c[e] = ok ? cb[o2] : 0.0f;
+            in.c[e] = (ok && (ntl > 1 || item == 0)) ? cb[o2] : 0.0f;   // (one tile: the c of this frame was the item before's c_prev)
             in.cp[e] = (ok && n > 0) ? cpb[o2] : 0.0f;
             in.dy[e] = ok ? dyb[o2] : (bf16_t)0;
             in.dcr[e] = (ok && n < T - 1 && ntl > 1) ? dcb[o1b + (unsigned)(re(e) * H)] : 0.0f;   // (one tile: carried in registers)
@@ -514,9 +537,11 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     Inputs in0, in1;                                     // two sets used in turn, as in the forward kernel
     issue_inputs(0, in0);
     __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): see the forward kernel
-    float dccarry[EPT];                                  // one tile per workgroup: its dE/dc of the frame visited before
+    // One tile per workgroup: dE/dc of the frame visited before and that frame's c_prev (this frame's c) stay in
+    // registers; a wavefront can have 63 vector-memory operations in flight, and an item of this kernel issues about 50.
+    float dccarry[EPT], ccarry[EPT];
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) dccarry[e] = 0.0f;
+    for (int e = 0; e < EPT; ++e) { dccarry[e] = 0.0f; ccarry[e] = 0.0f; }
     uint4 apre[MULTI ? 8 : 1];                           // first slab of the next item, loaded ahead (several tiles only)
     bool have_pre = false;
     auto do_item = [&](const int item, const Inputs& cur, Inputs& nxt) __attribute__((always_inline)) {
@@ -616,6 +641,9 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         float dcr[EPT];
 #pragma unroll
         for (int e = 0; e < EPT; ++e) dcr[e] = (ntl == 1) ? dccarry[e] : cur.dcr[e];
+        float cthis[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) cthis[e] = (ntl == 1 && item > 0) ? ccarry[e] : cur.c[e];
         if (KW > 128 && item + 1 < nitems) issue_inputs(item + 1, nxt);
         float dcf[EPT];
         unsigned dav[EPT][2];                             // (i, f) and (g, o) as bf16 pairs: kept for the row-major copy below
@@ -625,7 +653,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
             const float gi = bf2f((bf16_t)(cur.g[e].x & 0xFFFFu)), gf = bf2f((bf16_t)(cur.g[e].x >> 16));
             const float gg = bf2f((bf16_t)(cur.g[e].y & 0xFFFFu)), go = bf2f((bf16_t)(cur.g[e].y >> 16));
             const float dht = dh[e] + bf2f(cur.dy[e]);
-            const float tc = fast_tanh(cur.c[e]);
+            const float tc = fast_tanh(cthis[e]);
             const float dc = dht * go * (1.0f - tc * tc) + dcr[e];
             const float da_o = dht * tc * go * (1.0f - go);
             const float da_i = dc * gg * gi * (1.0f - gi);
@@ -634,15 +662,36 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
             dcf[e] = dc * gf;
             dav[e][0] = (unsigned)coh_bf16(da_i) | ((unsigned)coh_bf16(da_f) << 16);
             dav[e][1] = (unsigned)coh_bf16(da_g) | ((unsigned)coh_bf16(da_o) << 16);
-            if (FULL || b0 + rb + re(e) < B) {
-                bf16_t* xp = dxb + (oxs + (unsigned)(re(e) * 8));       // gate g: H columns = H/16 chunk pairs further
+        }
+        // A lane holds four rows of one unit; a 16-byte word of either copy of dE/da is eight units of one row.
+        // Regrouped through LDS inside the wavefront (its LDS operations execute in order), every lane ends up with
+        // the eight units of one (row, pair of gates): two 16-byte stores per copy instead of sixteen 2-byte ones
+        // (the memory pipeline takes about as long for a 2-byte store of a wavefront as for a 16-byte one).
+        static_assert(EPT == 4, "the regrouping below is written for four rows per lane");
+        unsigned* xs = reinterpret_cast<unsigned*>(lds) + NW * 4 * 64 * 4 + wave * 512;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const bf16_t v = (bf16_t)(dav[e][g >> 1] >> (16 * (g & 1)));
-                    if (SENTINEL) __hip_atomic_store(xp + (unsigned)(g * (H / 16) * XPAIR), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    else xp[(unsigned)(g * (H / 16) * XPAIR)] = v;
-                }
-            }
+        for (int e = 0; e < EPT; ++e) {
+            xs[((lh * 4 + e) * 2 + 0) * 32 + l32] = dav[e][0];
+            xs[((lh * 4 + e) * 2 + 1) * 32 + l32] = dav[e][1];
+        }
+        const int xk = lane & 3, xq = (lane >> 2) & 1, xr = (lane >> 3) & 3, xl = lane >> 5;
+        uint4 cga, cgb;                                   // gate 2 xq and gate 2 xq + 1, units 8 xk .. 8 xk + 7, row xrow
+        {
+            const uint4* src = reinterpret_cast<const uint4*>(xs + ((xl * 4 + xr) * 2 + xq) * 32 + 8 * xk);
+            const uint4 w0 = src[0], w1 = src[1];
+            cga = make_uint4(__builtin_amdgcn_perm(w0.y, w0.x, 0x05040100u), __builtin_amdgcn_perm(w0.w, w0.z, 0x05040100u),
+                             __builtin_amdgcn_perm(w1.y, w1.x, 0x05040100u), __builtin_amdgcn_perm(w1.w, w1.z, 0x05040100u));
+            cgb = make_uint4(__builtin_amdgcn_perm(w0.y, w0.x, 0x07060302u), __builtin_amdgcn_perm(w0.w, w0.z, 0x07060302u),
+                             __builtin_amdgcn_perm(w1.y, w1.x, 0x07060302u), __builtin_amdgcn_perm(w1.w, w1.z, 0x07060302u));
+        }
+        const int xrow = 2 * EPT * wave + 4 * xl + xr;    // row of the tile
+        const bool xok = FULL || b0 + xrow < B;
+        const unsigned xcol = (unsigned)(2 * xq * H + u * 32 + 8 * xk);   // column of gate 2 xq within the direction; + H: gate 2 xq + 1
+        if (xok) {
+            bf16_t* pa = dxb + ((xcol >> 3) * 256u + (unsigned)xrow * 8u);
+            bf16_t* pb = dxb + (((xcol + (unsigned)H) >> 3) * 256u + (unsigned)xrow * 8u);
+            if (SENTINEL) { st_coh_16B(pa, cga); st_coh_16B(pb, cgb); }
+            else { *reinterpret_cast<uint4*>(pa) = cga; *reinterpret_cast<uint4*>(pb) = cgb; }
         }
         if (KW <= 128 && item + 1 < nitems) issue_inputs(item + 1, nxt);
         if (SENTINEL) lds_barrier();
@@ -650,16 +699,19 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         // row-major dE/da for the weight- and input-gradient products, and the carried dE/dc
         float* dcb = a.dc + ((size_t)d * B + b0) * H;
         bf16_t* dab = a.da + ((size_t)t * B + b0) * 8 * H;
+        if (xok) {
+            bf16_t* pr = dab + ((unsigned)xrow * (unsigned)(8 * H) + (unsigned)(d * 4 * H) + xcol);
+            *reinterpret_cast<uint4*>(pr) = cga;
+            *reinterpret_cast<uint4*>(pr + H) = cgb;
+        }
+        if (ntl > 1) {
 #pragma unroll
-        for (int e = 0; e < EPT; ++e)
-            if (FULL || b0 + rb + re(e) < B) {
-                dcb[o1b + (unsigned)(re(e) * H)] = dcf[e];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) dab[o8b + (unsigned)((re(e) * 8 + g) * H)] = (bf16_t)(dav[e][g >> 1] >> (16 * (g & 1)));
-            }
+            for (int e = 0; e < EPT; ++e)
+                if (FULL || b0 + rb + re(e) < B) dcb[o1b + (unsigned)(re(e) * H)] = dcf[e];
+        }
         // next item's inputs; with one tile per workgroup its carried dE/dc is the one just computed
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) dccarry[e] = dcf[e];
+        for (int e = 0; e < EPT; ++e) { dccarry[e] = dcf[e]; ccarry[e] = cur.cp[e]; }
     };
     if constexpr (KW <= 128) {
         for (int item = 0; item < nitems; item += 2) {
@@ -744,7 +796,7 @@ hipError_t prepare(K kernel, int threads, size_t dyn_lds, int grid, bool* fits) 
 
 template <int NW, int KW, bool S, bool FULL, bool MULTI>
 hipError_t run_fwd_m(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
-    const size_t lds = (size_t)NW * 4 * 4 * 64 * 16;
+    const size_t lds = (size_t)NW * 4 * 4 * 64 * 16 + (size_t)NW * 512;   // partial sums; regrouping of h, 512 bytes per wavefront
     bool fits = false;
     hipError_t e = prepare(rec_fwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &fits);
     if (e != hipSuccess || !fits) return e;
@@ -762,7 +814,7 @@ hipError_t run_fwd(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched
 }
 template <int NW, int KW, bool S, bool FULL, bool MULTI>
 hipError_t run_bwd_m(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
-    const size_t lds = (size_t)NW * 4 * 64 * 16;
+    const size_t lds = (size_t)NW * 4 * 64 * 16 + (size_t)NW * 2048;   // partial sums; regrouping of dE/da, 2 KB per wavefront
     bool fits = false;
     hipError_t e = prepare(rec_bwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &fits);
     if (e != hipSuccess || !fits) return e;
