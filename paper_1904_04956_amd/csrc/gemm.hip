@@ -521,7 +521,7 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
         // Full 128x128 tile: stage it through LDS (free after the loop's last barrier) so that every
         // store instruction writes whole rows of the tile, 16 bytes (float) or 8 bytes (bf16) per lane.
         // 16-byte column groups are XOR-swizzled with the row so both sides spread over the banks.
-        if (sizeof(TO) == 2 && P.c_vec && !add) {   // (float rows already leave as full 128-byte segments)
+        if (P.c_vec && !add) {   // (a wavefront's 4-byte store costs the memory pipeline as much as a 16-byte one)
             float* cs = reinterpret_cast<float*>(smem);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
