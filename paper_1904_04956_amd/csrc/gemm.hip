@@ -54,7 +54,8 @@ struct Params {
     float* partial;                 // split-K: float [batch][splits][M][N], or null
     float* rs_partial;              // split-K: float [batch][splits][M] row sums
     int M, N, ntm, ntn, splits;
-    int c_vec;                      // C rows may be written with 16-byte (float) / 8-byte (bf16) stores
+    int c_vec;                      // C rows may be written with 16-byte (float) / 8-byte (bf16) stores, whole tiles of them
+    int p_vec;                      // the same for the float partial tiles of a split
     long long sA[2], sB[2], sC, sBias, sAdd, sRowsum;
 };
 
@@ -498,6 +499,58 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
     }
 
     // Epilogue: accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32.
+    if constexpr (FAST) {
+        // Full tiles go through LDS (free after the loop's last barrier), 128 tile rows at a time, so that every
+        // store instruction writes whole rows: 16 bytes (float) or 8 bytes (bf16) per lane.  A wavefront's 4-byte
+        // store costs the memory pipeline as much as a 16-byte one, and a tile has a quarter as many of the latter.
+        // The same for the float partial tiles of a split.  16-byte column groups are XOR-swizzled with the row so
+        // that both sides spread over the banks.
+        const bool to_part = P.splits > 1;
+        if (to_part ? P.p_vec != 0 : (P.c_vec != 0 && P.add == nullptr)) {
+            float* cs = reinterpret_cast<float*>(smem);
+            float* part = to_part ? P.partial + ((long long)z * P.splits + split) * (long long)P.M * P.N : nullptr;
+            TO* Cz = static_cast<TO*>(P.C) + z * P.sC;
+            const TI* bz = (!to_part && P.bias) ? static_cast<const TI*>(P.bias) + z * P.sBias : nullptr;
+            constexpr int RR = 128;                         // tile rows per round: RR x BN floats fill the LDS
+            static_assert(RR * BN * 4 <= 2 * STAGE * 16, "a round of the staged epilogue must fit the LDS of the main loop");
+            constexpr int GPR = BN / 4, RPP = NT / GPR;     // 16-byte groups per row, rows per pass of the stores
+#pragma unroll
+            for (int h = 0; h < BM / RR; ++h) {
+                if (h > 0) __syncthreads();
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int tr = wm * (32 * TM) + i * 32;                // first tile row of this accumulator block
+                    if (tr / RR != h) continue;                            // (uniform per wavefront)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int col = wn * (32 * TN) + j * 32 + (lane & 31);
+                        const float bv = bz ? ld_f(bz + col0 + col) : 0.0f;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int row = tr - h * RR + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                            cs[row * BN + ((((col >> 2) ^ (row & 7))) << 2) + (col & 3)] = acc[i][j][e] + bv;
+                        }
+                    }
+                }
+                __syncthreads();
+                const int g = tid % GPR;
+#pragma unroll 4
+                for (int pass = 0; pass < RR / RPP; ++pass) {
+                    const int r = pass * RPP + tid / GPR;
+                    const float4 v = *reinterpret_cast<const float4*>(&cs[r * BN + ((g ^ (r & 7)) << 2)]);
+                    const long long grow = row0 + h * RR + r;
+                    if (to_part) {
+                        *reinterpret_cast<float4*>(part + grow * P.N + col0 + 4 * g) = v;
+                    } else {
+                        TO* dst = Cz + grow * P.ldc + col0 + 4 * g;
+                        if constexpr (sizeof(TO) == 4) *reinterpret_cast<float4*>(dst) = v;
+                        else *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w));
+                    }
+                }
+            }
+            return;
+        }
+    }
     if (P.splits > 1) {
         float* part = P.partial + ((long long)z * P.splits + split) * (long long)P.M * P.N;
 #pragma unroll
@@ -517,40 +570,6 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
     TO* C = static_cast<TO*>(P.C) + z * P.sC;
     const TI* bias = P.bias ? static_cast<const TI*>(P.bias) + z * P.sBias : nullptr;
     const float* add = P.add ? P.add + z * P.sAdd : nullptr;
-    if constexpr (FAST && TM == 2 && TN == 2 && WN == 2) {
-        // Full 128x128 tile: stage it through LDS (free after the loop's last barrier) so that every
-        // store instruction writes whole rows of the tile, 16 bytes (float) or 8 bytes (bf16) per lane.
-        // 16-byte column groups are XOR-swizzled with the row so both sides spread over the banks.
-        if (P.c_vec && !add) {   // (a wavefront's 4-byte store costs the memory pipeline as much as a 16-byte one)
-            float* cs = reinterpret_cast<float*>(smem);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = wn * 64 + j * 32 + (lane & 31);
-                const float bv = bias ? ld_f(bias + col0 + col) : 0.0f;
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int row = wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                        cs[row * 128 + ((((col >> 2) ^ (row & 7))) << 2) + (col & 3)] = acc[i][j][e] + bv;
-                    }
-            }
-            __syncthreads();
-            const int g = tid & 31;
-#pragma unroll 4
-            for (int pass = 0; pass < 16; ++pass) {
-                const int r = pass * 8 + (tid >> 5);
-                const float4 v = *reinterpret_cast<const float4*>(&cs[r * 128 + ((g ^ (r & 7)) << 2)]);
-                TO* dst = C + (long long)(row0 + r) * P.ldc + col0 + 4 * g;
-                if constexpr (sizeof(TO) == 4) {
-                    *reinterpret_cast<float4*>(dst) = v;
-                } else {
-                    *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w));
-                }
-            }
-            return;
-        }
-    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -701,6 +720,7 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     const int tile = plan.big_tile ? 256 : 128;
     const bool fast = can_run_fast<TI>(d, P, tile);
     if (fast && d.Npad > 0) P.c_vec = 0;                 // whole tiles are computed, the stores stop at column N
+    P.p_vec = (d.N % 4 == 0 && !(fast && d.Npad > 0)) ? 1 : 0;   // (the scratch itself is 256-byte aligned)
     P.ntm = (d.M + tile - 1) / tile; P.ntn = ((fast && d.Npad > 0 ? d.Npad : d.N) + tile - 1) / tile;
     P.splits = plan.splits;
     P.partial = plan.splits > 1 ? d.partial : nullptr;
