@@ -595,7 +595,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
                                                             TO* __restrict__ C, long long ldc, long long sC,
                                                             const TI* __restrict__ bias, long long sBias,
                                                             const float* __restrict__ rs_partial, float* __restrict__ rowsum,
-                                                            long long sRowsum) {
+                                                            long long sRowsum, int vec4) {
     const int z = blockIdx.z;
     const long long total = (long long)M * N;
     if (rowsum)
@@ -607,6 +607,23 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     const float* part = partial + (long long)z * splits * total;
     TO* Cz = C + z * sC;
     const TI* bz = bias ? bias + z * sBias : nullptr;
+    if (vec4) {                                          // N a multiple of 4, rows of C and of the partial tiles 16-byte aligned
+        const long long total4 = total >> 2;
+        const int n4 = N >> 2;
+        for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total4; i += (long long)gridDim.x * blockDim.x) {
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            for (int s = 0; s < splits; ++s) {
+                const float4 p4 = *reinterpret_cast<const float4*>(part + s * total + 4 * i);
+                v.x += p4.x; v.y += p4.y; v.z += p4.z; v.w += p4.w;
+            }
+            const int m = (int)(i / n4), n = (int)(i % n4) * 4;
+            if (bz) { v.x += ld_f(bz + n); v.y += ld_f(bz + n + 1); v.z += ld_f(bz + n + 2); v.w += ld_f(bz + n + 3); }
+            TO* dst = &Cz[(long long)m * ldc + n];
+            if constexpr (sizeof(TO) == 4) *reinterpret_cast<float4*>(dst) = v;
+            else *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w));
+        }
+        return;
+    }
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
         float v = 0.0f;
         for (int s = 0; s < splits; ++s) v += part[s * total + i];
@@ -735,7 +752,7 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
         unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
         hipLaunchKernelGGL((splitk_reduce_kernel<TI, TO>), dim3(blocks, 1, batch), dim3(256), 0, stream, d.partial, plan.splits,
                            d.M, d.N, static_cast<TO*>(d.C), d.ldc, d.sC, static_cast<const TI*>(d.bias), d.sBias,
-                           P.rs_partial, d.rowsum, d.sRowsum);
+                           P.rs_partial, d.rowsum, d.sRowsum, (P.c_vec && d.N % 4 == 0) ? 1 : 0);
         return hipGetLastError();
     }
     return plan.big_tile ? launch_form<TI, TO, 4, 2, 4>(d, P, fast, false, grid, stream) : launch_form<TI, TO, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
