@@ -518,13 +518,13 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
             for (int h = 0; h < BM / RR; ++h) {
                 if (h > 0) __syncthreads();
 #pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    const int tr = wm * (32 * TM) + i * 32;                // first tile row of this accumulator block
-                    if (tr / RR != h) continue;                            // (uniform per wavefront)
+                for (int j = 0; j < TN; ++j) {
+                    const int col = wn * (32 * TN) + j * 32 + (lane & 31);
+                    const float bv = bz ? ld_f(bz + col0 + col) : 0.0f;
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const int col = wn * (32 * TN) + j * 32 + (lane & 31);
-                        const float bv = bz ? ld_f(bz + col0 + col) : 0.0f;
+                    for (int i = 0; i < TM; ++i) {
+                        const int tr = wm * (32 * TM) + i * 32;            // first tile row of this accumulator block
+                        if (tr / RR != h) continue;                        // (uniform per wavefront)
 #pragma unroll
                         for (int e = 0; e < 16; ++e) {
                             const int row = tr - h * RR + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
@@ -534,15 +534,20 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
                 }
                 __syncthreads();
                 const int g = tid % GPR;
+                if (to_part) {
+                    float* dst0 = part + (long long)(row0 + h * RR) * P.N + col0 + 4 * g;
 #pragma unroll 4
-                for (int pass = 0; pass < RR / RPP; ++pass) {
-                    const int r = pass * RPP + tid / GPR;
-                    const float4 v = *reinterpret_cast<const float4*>(&cs[r * BN + ((g ^ (r & 7)) << 2)]);
-                    const long long grow = row0 + h * RR + r;
-                    if (to_part) {
-                        *reinterpret_cast<float4*>(part + grow * P.N + col0 + 4 * g) = v;
-                    } else {
-                        TO* dst = Cz + grow * P.ldc + col0 + 4 * g;
+                    for (int pass = 0; pass < RR / RPP; ++pass) {
+                        const int r = pass * RPP + tid / GPR;
+                        *reinterpret_cast<float4*>(dst0 + (long long)r * P.N) = *reinterpret_cast<const float4*>(&cs[r * BN + ((g ^ (r & 7)) << 2)]);
+                    }
+                } else {
+                    TO* dst0 = Cz + (long long)(row0 + h * RR) * P.ldc + col0 + 4 * g;
+#pragma unroll 4
+                    for (int pass = 0; pass < RR / RPP; ++pass) {
+                        const int r = pass * RPP + tid / GPR;
+                        const float4 v = *reinterpret_cast<const float4*>(&cs[r * BN + ((g ^ (r & 7)) << 2)]);
+                        TO* dst = dst0 + (long long)r * P.ldc;
                         if constexpr (sizeof(TO) == 4) *reinterpret_cast<float4*>(dst) = v;
                         else *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w));
                     }
