@@ -29,11 +29,11 @@ PEAK_HBM = 8.0e12            # B/s
 # (FETCH_SIZE and WRITE_SIZE, each scaled by its reading for the 1 GiB copy of --traffic-calibration);
 # the runs and figures are in profiles/hbm_traffic_paper4x512.txt.  Keyed by (workload, batch, class).
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    ("paper4x512", 256, "recurrent_bwd_persistent"): (2 * 74711.1 + 129024.0) * 1024,
-    ("paper4x512", 256, "recurrent_fwd_persistent"): (2 * 64668.1 + 86016.0) * 1024,
-    ("paper4x512", 256, "gemm_logits"): (2 * 51884.2 + 336000.0) * 1024,
+    ("paper4x512", 256, "recurrent_bwd_persistent"): (2 * 74703.8 + 129024.0) * 1024,
+    ("paper4x512", 256, "recurrent_fwd_persistent"): (2 * 64671.3 + 86016.1) * 1024,
+    ("paper4x512", 256, "gemm_logits"): (2 * 51944.5 + 336000.0) * 1024,
     # nine launches per step: dW_x of layers 0-3 and dW_p (one kernel name, five launches), four dU_h
-    ("paper4x512", 256, "gemm_wgrad"): (2 * (5 * 75978.0 + 4 * 92285.5) + (5 * 13228.4 + 4 * 16384.0)) * 1024 / 9,
+    ("paper4x512", 256, "gemm_wgrad"): (2 * (5 * 75956.3 + 4 * 92284.0) + (5 * 13228.6 + 4 * 16384.0)) * 1024 / 9,
 }
 MEASURED_MIX_BYTES_PER_PAIR = {"paper4x512": (2 * 119318.0 + 357967.2) * 1024}   # one launch on two replicas
 
