@@ -343,7 +343,8 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
                 }
                 pa.count = 3; pa.cols = Din; pa.cols_p = ctx->Dp;
                 RUN(PC_MISC, "padded copies of x and W_x", launch_pad_cols(pa, st));
-                d.seg[0] = GemmSeg{XP, WP, ctx->Dp, ctx->Dp, 0, (long long)4 * H * ctx->Dp, ctx->Dp};
+                // (rows are Dp long for the weight gradient's whole tiles; the contraction needs whole slabs of 64 only)
+                d.seg[0] = GemmSeg{XP, WP, ctx->Dp, ctx->Dp, 0, (long long)4 * H * ctx->Dp, (Din + 63) / 64 * 64};
             }
             d.C = AX; d.ldc = 8 * H; d.sC = 4 * H;
             d.bias = at(theta, ctx->off_b[0][l], e); d.sBias = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);
