@@ -138,8 +138,9 @@ int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
 /* BLSTM_OPT_RECURRENT_SYNC (default 1): how the workgroups of a persistent kernel exchange h / dE/da
    between frames.  0: plain accesses ordered by agent-scope release/acquire fences around a counter.
    1: the exchanged tensor is pre-filled with a bf16 NaN pattern no result can take; elements are
-   stored write-through and loaded cache-bypassing at agent scope, and a consumer proceeds once
-   none of the elements it needs still holds the pattern (each element is its own ready flag). */
+   stored write-through at agent scope, and a consumer proceeds once none of the elements it needs
+   still holds the pattern (each element is its own ready flag: written once, so any other value is
+   final whatever cache answered; elements that still show the pattern are re-read cache-bypassing). */
 #define BLSTM_OPT_RECURRENT_SYNC 2
 /* BLSTM_OPT_OVERLAP: 1 = blstm_backward runs the weight-gradient products on a second stream owned by
    the context (default priority), forked from and joined to the caller's stream with events, so that
