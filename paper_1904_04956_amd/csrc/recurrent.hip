@@ -284,6 +284,29 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     // chunks are loaded while this item computes (checked for the sentinel like any other load).
     uint4 apre[MULTI ? KSTEPS : 1];
     bool have_pre = false;
+    // The row-major outputs of an item (c, the gates, h for the next layer) are not on the frame-to-frame path:
+    // they wait in registers until the next item has issued its loads of the exchanged h, and go out behind them.
+    struct Tail { int t, b0; bool have, xok; float cn[EPT]; uint2 g[EPT]; uint2 hq; } tail;
+    tail.have = false;
+    auto flush_tail = [&]() __attribute__((always_inline)) {
+        if (!tail.have) return;
+        tail.have = false;
+        float* cb = a.c + ((size_t)tail.t * B + tail.b0) * 2 * H;
+        bf16_t* yb = a.y + ((size_t)tail.t * B + tail.b0) * 2 * H;
+        bf16_t* gb = a.gates + ((size_t)tail.t * B + tail.b0) * 8 * H;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            if (FULL || tail.b0 + rb + re(e) < B) {
+                cb[o2b + (unsigned)(re(e) * 2 * H)] = tail.cn[e];
+                // the four gate activations of a unit are one 8-byte word: [frame row][direction][unit][gate]
+                *reinterpret_cast<uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) = tail.g[e];
+            }
+        }
+        const int lane_ = threadIdx.x & 63;
+        const int xrow_ = 2 * EPT * (int)(threadIdx.x >> 6) + 4 * (lane_ >> 5) + ((lane_ >> 3) & 3);
+        const unsigned xcol_ = (unsigned)(u * 32 + 8 * ((lane_ >> 1) & 3) + 4 * (lane_ & 1));
+        if (tail.xok) *reinterpret_cast<uint2*>(yb + ((unsigned)xrow_ * (unsigned)(2 * H) + (unsigned)(d * H) + xcol_)) = tail.hq;
+    };
     auto do_item = [&](const int item, const float (&ax)[EPT][4], const float (&cpl)[EPT], float (&axn)[EPT][4],
                        float (&cpn)[EPT]) __attribute__((always_inline)) {
         const int n = item / ntl, i = item - n * ntl;
@@ -322,6 +345,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                     // (The widest slice has no registers for two attempts: probe first, then the data.)
                     if constexpr (KW <= 128) {
                         load_chunks_cached<KSTEPS>(afrag, hp, valid);
+                        flush_tail();
                         if (!all_written<KSTEPS>(afrag)) {
                             gu = wait_probe(probe, lane < KW / 32, a.abort_word, a.limit_ticks);
                             asm volatile("" ::: "memory");
@@ -390,6 +414,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         // (The next item's inputs come from HBM, and a CU's vector memory pipeline returns data in order: issued
         // before the barrier above they would sit in front of another wavefront's loads of the exchanged h and
         // add their latency to the frame-to-frame path.  They are issued below, once h has gone out.)
+        flush_tail();                                     // at the latest here: the loads issued below may read what it stores
         float cp[EPT];
 #pragma unroll
         for (int e = 0; e < EPT; ++e) cp[e] = (ntl == 1) ? ccarry[e] : cpl[e];
@@ -430,20 +455,13 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         if (KW <= 128 && item + 1 < nitems) issue_inputs(item + 1, axn, cpn);
         if (SENTINEL) lds_barrier();                     // frees the LDS buffer for the next item
         else signal_counter(cnt + i);                    // barrier inside: same role
-        // row-major outputs (h for the next layer, c and the gates for the backward pass): off the
-        // critical path of the exchange
-        float* cb = a.c + ((size_t)t * B + b0) * 2 * H;
-        bf16_t* yb = a.y + ((size_t)t * B + b0) * 2 * H;
-        bf16_t* gb = a.gates + ((size_t)t * B + b0) * 8 * H;
+        // row-major outputs (h for the next layer, c and the gates for the backward pass): kept for flush_tail
+        tail.t = t; tail.b0 = b0; tail.have = true; tail.xok = xok; tail.hq = hq;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            if (FULL || b0 + rb + re(e) < B) {
-                cb[o2b + (unsigned)(re(e) * 2 * H)] = cn[e];
-                // the four gate activations of a unit are one 8-byte word: [frame row][direction][unit][gate]
-                *reinterpret_cast<uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) = make_uint2(pack_bf2(gi[e], gf[e]), pack_bf2(gg[e], go[e]));
-            }
+            tail.cn[e] = cn[e];
+            tail.g[e] = make_uint2(pack_bf2(gi[e], gf[e]), pack_bf2(gg[e], go[e]));
         }
-        if (xok) *reinterpret_cast<uint2*>(yb + ((unsigned)xrow * (unsigned)(2 * H) + (unsigned)(d * H) + xcol)) = hq;
         // with one tile per workgroup the next item's previous cell state is the one just computed
 #pragma unroll
         for (int e = 0; e < EPT; ++e) ccarry[e] = cn[e];
@@ -465,6 +483,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             }
         }
     }
+    flush_tail();
 }
 
 // ------------------------------------------------------------------------------ backward
