@@ -18,7 +18,9 @@ blocking, fusion or reordering:
   * update (paper Eq. 1c): theta <- theta - alpha * g  (with momentum mu:
     v <- mu*v + g ; theta <- theta - alpha*v);
   * decentralised averaging (paper Eq. 4, second line, and the sender/receiver
-    pairing of section 3.2): both members of a pair take (theta_i + theta_j)/2.
+    pairing of section 3.2): both members of a pair take (theta_i + theta_j)/2;
+  * the orders in which section 3.2's strategies call these (Fig. 3a SYNC, Fig. 3b stale
+    ADPSGD, Fig. 3c HYBRID), as functions of the learners' weights and gradients.
 
 Flat parameter layout (row-major, gate blocks in the order i, f, g, o):
   for layer l = 0..L-1, for direction d in (forward, backward):
@@ -341,3 +343,15 @@ def stale_adpsgd_step(thetas, grads, partner, lr):
     computed on thetas[i]; the gradient is therefore one averaging step stale when it is applied."""
     pulled = adpsgd_mix(thetas, partner)
     return [sgd_step(pulled[i], grads[i], lr)[0] for i in range(len(thetas))]
+
+
+def hybrid_step(pushed, grads, lr):
+    """One iteration of HYBRID in the integration order of Fig. 3c, whose push is an AllReduce over all
+    learners (section 3.2): g = calGrad(W) on the weights W the learner pulled in the iteration before,
+    W = pull_weights() = the mean of what all learners pushed at the end of that iteration,
+    W' = apply(W, g), push_weights(W').  pushed[i] is learner i's W' of the iteration before and grads[i]
+    its gradient on the W it pulled then, so the gradient is one iteration stale when applied (Table 1).
+    Returns (pushed_new, pulled): the W' the learners push now, and the common W they hold for the next
+    gradient.  Before the first iteration every learner holds and has pushed the common initial weights."""
+    pulled = np.mean(np.stack([np.asarray(t, dtype=np.float64) for t in pushed]), axis=0)
+    return [sgd_step(pulled, grads[i], lr)[0] for i in range(len(pushed))], pulled

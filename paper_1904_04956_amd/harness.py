@@ -45,6 +45,7 @@ class Learner:
         self.z = torch.zeros((T, B, self.zdim), dtype=self.act_dtype, device=dev)
         self.dz = torch.zeros((T, B, self.zdim), dtype=self.act_dtype, device=dev)
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.held = None          # HYBRID only: the pulled weights the next gradient is taken on
 
     def close(self):
         if self.ctx is not None:
@@ -77,9 +78,10 @@ class Learner:
     def forward(self, stream=None):
         bl.blstm_forward(self.ctx, self.theta_fwd, self.x, self.z, stream)
 
-    def calgrad(self, stream=None):
-        """g = calGrad(W): forward, softmax cross-entropy, backward."""
-        th = self.theta_fwd
+    def calgrad(self, stream=None, weights=None):
+        """g = calGrad(W): forward, softmax cross-entropy, backward (on `weights` if given, in the
+        storage type of the mode, else on the learner's own)."""
+        th = self.theta_fwd if weights is None else weights
         bl.blstm_forward(self.ctx, th, self.x, self.z, stream)
         bl.softmax_xent_fwd_bwd(self.ctx, th, self.z, self.labels, self.loss, self.dz, self.grad, stream)
         bl.blstm_backward(self.ctx, th, self.x, self.dz, self.grad, stream)
@@ -87,6 +89,13 @@ class Learner:
     def apply(self, lr, stream=None):
         """W' = apply(W, g)."""
         bl.sgd_step(self.theta, self.shadow, self.grad, self.n, lr, self.momentum, self.velocity, stream)
+
+    def hold(self):
+        """Keeps a copy of the weights as forward/backward read them now (a device-to-device copy on
+        torch's current stream): what pull_weights() returned, for the next iteration's gradient."""
+        if self.held is None:
+            self.held = torch.empty_like(self.theta_fwd)
+        self.held.copy_(self.theta_fwd)
 
     def train_step(self, lr, stream=None):
         self.calgrad(stream)
@@ -164,3 +173,18 @@ def sync_step(learners, lr, stream=None):
     masters = [l.theta for l in learners]
     shadows = [l.shadow for l in learners] if learners[0].shadow is not None else None
     bl.sync_average(masters, shadows, learners[0].n, len(learners), stream)
+
+
+def hybrid_step(learners, lr):
+    """HYBRID of Fig. 3c with its push as an average over all learners (section 3.2): the gradient is taken
+    on the weights pulled in the iteration before (the common initial weights at first), the pull is the
+    mean of what every learner pushed at the end of that iteration (sync_average over the masters), and the
+    gradient is applied to the pulled weights.  Runs on the default stream (the held copy is a torch copy)."""
+    for l in learners:
+        l.calgrad(weights=l.held)
+    masters = [l.theta for l in learners]
+    shadows = [l.shadow for l in learners] if learners[0].shadow is not None else None
+    bl.sync_average(masters, shadows, learners[0].n, len(learners))
+    for l in learners:
+        l.hold()
+        l.apply(lr)

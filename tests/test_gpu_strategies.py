@@ -1,5 +1,5 @@
 """GPU parity of the strategy rows beyond plain ADPSGD: the fused pair update (Eq. 4 in one pass), the
-synchronous R-way average (Fig. 3a) and the stale integration order of Fig. 3b, through the C-ABI,
+synchronous R-way average (Fig. 3a), the stale integration order of Fig. 3b and HYBRID (Fig. 3c), through the C-ABI,
 against the float64 oracle.  Tolerances: streaming kernels 1e-6 relative (fp32 arithmetic on fp32
 data); whole training steps 1e-4 (fp32 mode), per tensor max|gpu - ref| / max|ref|."""
 import sys
@@ -150,6 +150,35 @@ def test_adpsgd_orders_against_the_oracle(order):
     assert worst <= 1e-4
     if order == "stale":      # after the apply the members of a pair differ again (each used its own gradient)
         assert not np.array_equal(ls[0].theta_numpy(), ls[partner[0]].theta_numpy())
+    for l in ls:
+        l.close()
+
+
+def test_hybrid_order_against_the_oracle():
+    """Fig. 3c on four learners, six iterations: each gradient is taken on the weights pulled one iteration
+    earlier and applied to the mean of what all learners pushed (sync_average), against the oracle's hybrid_step."""
+    from paper_1904_04956_amd.harness import hybrid_step
+    R, iters, lr = 4, 6, 0.08
+    dims = dict(T=9, B=6, D=24, H=32, L=2, P=16, V=150)
+    dm = orc.Dims(**dims)
+    theta0 = inputs.make_theta(orc.param_count(dm), 33)
+    ls = _learners(dims, R, 0, theta0)
+    pushed = [theta0.astype(np.float64) + 0.0 for _ in range(R)]
+    held = theta0.astype(np.float64)
+    for it in range(iters):
+        grads = []
+        for r, l in enumerate(ls):
+            x, labels = inputs.make_batch(dm.T, dm.B, dm.D, dm.V, 1200 + R * it + r)
+            l.set_batch(x, labels)
+            grads.append(orc.loss_and_grad(dm, held, x, labels)[1])
+        hybrid_step(ls, lr)
+        pushed, held = orc.hybrid_step(pushed, grads, lr)
+        assert all(np.array_equal(ls[0].held.cpu().numpy(), l.held.cpu().numpy()) for l in ls[1:])   # one common pull
+        assert rel_err(ls[0].held.cpu().numpy(), held) <= 1e-4
+    worst = max(rel_err(l.theta_numpy(), pushed[r]) for r, l in enumerate(ls))
+    say(f"HYBRID, {iters} iterations, {R} learners: worst relative error of the pushed weights {worst:.2e}")
+    assert worst <= 1e-4
+    assert not np.array_equal(ls[0].theta_numpy(), ls[1].theta_numpy())     # each applied its own gradient
     for l in ls:
         l.close()
 

@@ -497,3 +497,35 @@ def test_stale_adpsgd_order_by_hand_and_its_reductions():
     # lr = 0: pure mixing
     mixed = orc.stale_adpsgd_step([a, ga], [a, a], [1, 0], 0.0)
     assert np.array_equal(mixed[0], (a + ga) / 2)
+
+
+def test_hybrid_order_by_hand_and_its_reductions():
+    # Fig. 3c on scalars, two learners: pushed (1, 3), gradients (0.5, -1.5), lr 0.1:
+    # pull = 2; apply: (2 - 0.05, 2 + 0.15)
+    new, pulled = orc.hybrid_step([np.array([1.0]), np.array([3.0])], [np.array([0.5]), np.array([-1.5])], 0.1)
+    assert pulled[0] == 2.0 and new[0][0] == pytest.approx(1.95) and new[1][0] == pytest.approx(2.15)
+    # one learner on E = w^2 / 2 (gradient = the weights it evaluates on), lr 0.5, w = 1: the gradient of an
+    # iteration is taken on the weights pulled one iteration earlier, so W' runs 0.5, 0, -0.25
+    # (plain SGD, Eq. 1c, would give 0.5, 0.25, 0.125)
+    pushed, held = [np.array([1.0])], np.array([1.0])
+    seen = []
+    for _ in range(3):
+        g = [held.copy()]
+        pushed, held = orc.hybrid_step(pushed, g, 0.5)
+        seen.append(pushed[0][0])
+    assert seen == [0.5, 0.0, -0.25]
+    # the mean of what is pushed follows the one-step-stale large-batch update: mean W' = pull - lr mean g
+    rng = np.random.default_rng(6)
+    R, n = 5, 20
+    pushed = [rng.standard_normal(n) for _ in range(R)]
+    grads = [rng.standard_normal(n) for _ in range(R)]
+    new, pulled = orc.hybrid_step(pushed, grads, 0.3)
+    assert np.allclose(pulled, np.mean(np.stack(pushed), axis=0), rtol=0, atol=1e-15)
+    assert np.allclose(np.mean(np.stack(new), axis=0), pulled - 0.3 * np.mean(np.stack(grads), axis=0), rtol=0, atol=1e-14)
+    # the pull is the uniform mixing matrix of SYNC (Fig. 3a) applied to the pushed weights
+    assert np.array_equal(pulled, orc.sync_average(pushed)[0])
+    # equal gradients: every learner pushes the same vector; lr = 0: pure averaging
+    same, _ = orc.hybrid_step(pushed, [grads[0]] * R, 0.3)
+    assert all(np.array_equal(same[0], t) for t in same[1:])
+    avg, _ = orc.hybrid_step(pushed, grads, 0.0)
+    assert all(np.array_equal(a, pulled) for a in avg)
