@@ -90,6 +90,20 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
 int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const int32_t* labels,
                          float* loss_dev, void* dz, float* grad, void* stream);
 
+/* softmax_xent_fwd_bwd for callers that cannot allocate device memory or bind a workspace at that point
+   (code under stream capture, tight serving loops, harnesses that forbid allocation): same arguments, same
+   kernels and same results, but the scratch of the call (the logit matrix [T*B][V] in the storage type, one
+   loss term per frame, partial tiles of the products split along the contraction) lives in an array of
+   BLSTM_NOALLOC_SCRATCH_BYTES inside the library's code object instead of the bound workspace; no workspace
+   needs to be bound.  Each GPU the library runs on holds that array until the process ends.  The call
+   allocates and frees nothing.  Shapes whose scratch exceeds the array are rejected with
+   BLSTM_ERR_WORKSPACE before any launch (roughly T*B*V*2 bytes in mode 1, *4 in mode 0, plus a few MB).
+   All calls on one GPU share the array: calls that overlap on one GPU (different streams or threads) race;
+   everything the call reads from the array it has written itself earlier in the same call. */
+#define BLSTM_NOALLOC_SCRATCH_BYTES (32u << 20)
+int softmax_xent_fwd_bwd_noalloc(blstm_ctx* ctx, const void* theta, const void* z, const int32_t* labels,
+                                 float* loss_dev, void* dz, float* grad, void* stream);
+
 /* Back-propagation through the bottleneck and through time (Eq. 1b): writes every slice of grad
    except W_s and b_s.  Must follow blstm_forward on the same ctx, theta and x. */
 int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void* dz, float* grad, void* stream);

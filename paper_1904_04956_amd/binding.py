@@ -19,7 +19,7 @@ BLSTM_MAX_REPLICAS = 64
 
 EXPORTS = [
     "blstm_create", "blstm_destroy", "blstm_param_count", "blstm_workspace_bytes", "blstm_param_offset",
-    "blstm_bind", "blstm_forward", "softmax_xent_fwd_bwd", "blstm_backward", "sgd_step", "adpsgd_mix",
+    "blstm_bind", "blstm_forward", "softmax_xent_fwd_bwd", "softmax_xent_fwd_bwd_noalloc", "blstm_backward", "sgd_step", "adpsgd_mix",
     "sgd_mix_pair", "sync_average", "blstm_lr_schedule",
     "adpsgd_ring_partner", "blstm_shadow_refresh", "blstm_set_option", "blstm_device_status", "blstm_profile_enable", "blstm_profile_read",
     "blstm_profile_classes", "blstm_profile_name", "blstm_last_error",
@@ -64,6 +64,8 @@ def lib():
     L.blstm_forward.restype = c_int
     L.softmax_xent_fwd_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     L.softmax_xent_fwd_bwd.restype = c_int
+    L.softmax_xent_fwd_bwd_noalloc.argtypes = L.softmax_xent_fwd_bwd.argtypes
+    L.softmax_xent_fwd_bwd_noalloc.restype = c_int
     L.blstm_backward.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     L.blstm_backward.restype = c_int
     L.sgd_step.argtypes = [c_void_p, c_void_p, c_void_p, c_size_t, c_float, c_float, c_void_p, c_void_p]
@@ -168,6 +170,11 @@ def softmax_xent_fwd_bwd(ctx, theta, z, labels, loss_dev, dz, grad, stream=None)
                                              _ptr(grad), _stream(stream)))
 
 
+def softmax_xent_fwd_bwd_noalloc(ctx, theta, z, labels, loss_dev, dz, grad, stream=None):
+    return _check(lib().softmax_xent_fwd_bwd_noalloc(ctx, _ptr(theta), _ptr(z), _ptr(labels), _ptr(loss_dev), _ptr(dz),
+                                                     _ptr(grad), _stream(stream)))
+
+
 def blstm_backward(ctx, theta, x, dz, grad, stream=None):
     return _check(lib().blstm_backward(ctx, _ptr(theta), _ptr(x), _ptr(dz), _ptr(grad), _stream(stream)))
 
@@ -218,6 +225,8 @@ def blstm_shadow_refresh(theta_master, theta_bf16, n, stream=None):
 BLSTM_OPT_RECURRENT_PATH = 1
 BLSTM_OPT_RECURRENT_SYNC = 2
 BLSTM_OPT_OVERLAP = 3
+BLSTM_OPT_TEST_ABORT = 4
+BLSTM_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
 def blstm_set_option(ctx, option, value):

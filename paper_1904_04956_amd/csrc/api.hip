@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -146,6 +147,77 @@ hipError_t ensure_side(blstm_ctx* c) {
 
 inline const char* at(const void* base, size_t elems, size_t esz) { return static_cast<const char*>(base) + elems * esz; }
 inline char* at(void* base, size_t elems, size_t esz) { return static_cast<char*>(base) + elems * esz; }
+
+
+// Scratch of the softmax cross-entropy: the logit matrix [M][V] (storage type, overwritten in place by dE/du),
+// one loss term per frame, and the float partial tiles of products split along K.
+struct SoftmaxScratch { char* logits; float* row_loss; float* partial; size_t partial_bytes; };
+
+int softmax_xent_run(blstm_ctx* ctx, const SoftmaxScratch& sc, const void* theta, const void* z, const int32_t* labels,
+                     float* loss_dev, void* dz, float* grad, hipStream_t st) {
+    const int M = ctx->M, V = ctx->V, Z = ctx->zdim;
+    const size_t e = ctx->esz;
+    const DType S = ctx->st;
+    char* U = sc.logits;
+    auto desc = [&](DType in, DType out) {
+        GemmDesc d = gemm_desc(ctx, in, out);
+        d.partial = sc.partial; d.partial_bytes = sc.partial_bytes;
+        return d;
+    };
+    {   // u = W_s z + b_s
+        GemmDesc d = desc(S, S);
+        d.M = M; d.N = V;
+        d.seg[0] = GemmSeg{z, at(theta, ctx->off_ws, e), Z, Z, 0, 0, Z};
+        d.C = U; d.ldc = V;
+        d.bias = at(theta, ctx->off_bs, e);
+        RUN(PC_GEMM_LOGITS, "logits", launch_gemm(d, st));
+    }
+    RUN(PC_SOFTMAX_ROWS, "softmax rows", launch_softmax_rows(U, V, labels, sc.row_loss, M, V, ctx->s, S, st));
+    RUN(PC_MISC, "loss sum", launch_sum_to_scalar(sc.row_loss, M, loss_dev, st));
+    {   // dz = du W_s
+        GemmDesc d = desc(S, S);
+        d.M = M; d.N = Z; d.btrans = true;
+        d.seg[0] = GemmSeg{U, at(theta, ctx->off_ws, e), V, Z, 0, 0, V};
+        d.C = dz; d.ldc = Z;
+        RUN(PC_GEMM_SOFTMAX_BWD, "dz", launch_gemm(d, st));
+    }
+    {   // dW_s = du^T z
+        GemmDesc d = desc(S, DT_F32);
+        d.M = V; d.N = Z; d.atrans = true; d.btrans = true;
+        d.seg[0] = GemmSeg{U, z, V, Z, 0, 0, M};
+        d.C = grad + ctx->off_ws; d.ldc = Z;
+        d.rowsum = grad + ctx->off_bs;                 // db_s = sum over frames of du
+        RUN(PC_GEMM_SOFTMAX_BWD, "dW_s", launch_gemm(d, st));
+    }
+    return BLSTM_OK;
+}
+
+// ---- scratch that lives in the library's own code object, for callers that cannot allocate --------------------
+// Each GPU the library runs on holds its own copy of this array, at its own address, until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: kernels are given the address that call
+// returns for the current device, looked up once per device.
+__device__ __align__(256) static unsigned char g_noalloc_scratch[BLSTM_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[kMaxDevices];                  // per device, null until looked up
+
+int resident_scratch(char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return check_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(BLSTM_ERR_DIM, "device index %d beyond the %d this library keeps scratch for", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch));     // the copy on the current device
+        if (e != hipSuccess) return check_hip(e, "hipGetSymbolAddress");
+        if (!p) return fail(BLSTM_ERR_HIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = static_cast<char*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return BLSTM_OK;
+}
 
 }  // namespace
 
@@ -422,38 +494,31 @@ int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const
     if (!ctx->ws) return fail(BLSTM_ERR_WORKSPACE, "softmax_xent_fwd_bwd: no workspace bound");
     if (!aligned16(theta) || !aligned16(z) || !aligned16(dz) || !aligned16(grad))
         return fail(BLSTM_ERR_ALIGN, "softmax_xent_fwd_bwd: pointers must be 16-byte aligned");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int M = ctx->M, V = ctx->V, Z = ctx->zdim;
-    const size_t e = ctx->esz;
-    const DType S = ctx->st;
-    char* U = ctx->ws + ctx->wLOGITS;
-    float* row_loss = reinterpret_cast<float*>(ctx->ws + ctx->wROWLOSS);
-    {   // u = W_s z + b_s
-        GemmDesc d = gemm_desc(ctx, S, S);
-        d.M = M; d.N = V;
-        d.seg[0] = GemmSeg{z, at(theta, ctx->off_ws, e), Z, Z, 0, 0, Z};
-        d.C = U; d.ldc = V;
-        d.bias = at(theta, ctx->off_bs, e);
-        RUN(PC_GEMM_LOGITS, "logits", launch_gemm(d, st));
-    }
-    RUN(PC_SOFTMAX_ROWS, "softmax rows", launch_softmax_rows(U, V, labels, row_loss, M, V, ctx->s, S, st));
-    RUN(PC_MISC, "loss sum", launch_sum_to_scalar(row_loss, M, loss_dev, st));
-    {   // dz = du W_s
-        GemmDesc d = gemm_desc(ctx, S, S);
-        d.M = M; d.N = Z; d.btrans = true;
-        d.seg[0] = GemmSeg{U, at(theta, ctx->off_ws, e), V, Z, 0, 0, V};
-        d.C = dz; d.ldc = Z;
-        RUN(PC_GEMM_SOFTMAX_BWD, "dz", launch_gemm(d, st));
-    }
-    {   // dW_s = du^T z
-        GemmDesc d = gemm_desc(ctx, S, DT_F32);
-        d.M = V; d.N = Z; d.atrans = true; d.btrans = true;
-        d.seg[0] = GemmSeg{U, z, V, Z, 0, 0, M};
-        d.C = grad + ctx->off_ws; d.ldc = Z;
-        d.rowsum = grad + ctx->off_bs;                 // db_s = sum over frames of du
-        RUN(PC_GEMM_SOFTMAX_BWD, "dW_s", launch_gemm(d, st));
-    }
-    return BLSTM_OK;
+    SoftmaxScratch sc{ctx->ws + ctx->wLOGITS, reinterpret_cast<float*>(ctx->ws + ctx->wROWLOSS),
+                      reinterpret_cast<float*>(ctx->ws + ctx->wPART), ctx->part_bytes};
+    return softmax_xent_run(ctx, sc, theta, z, labels, loss_dev, dz, grad, static_cast<hipStream_t>(stream));
+}
+
+int softmax_xent_fwd_bwd_noalloc(blstm_ctx* ctx, const void* theta, const void* z, const int32_t* labels,
+                                 float* loss_dev, void* dz, float* grad, void* stream) {
+    if (!ctx || !theta || !z || !labels || !loss_dev || !dz || !grad) return fail(BLSTM_ERR_NULL, "softmax_xent_fwd_bwd_noalloc: null argument");
+    if (!aligned16(theta) || !aligned16(z) || !aligned16(dz) || !aligned16(grad))
+        return fail(BLSTM_ERR_ALIGN, "softmax_xent_fwd_bwd_noalloc: pointers must be 16-byte aligned");
+    // layout of the resident array: logits, row losses, split-K partial tiles (whatever is left)
+    const size_t logits = up256((size_t)ctx->M * (size_t)ctx->V * ctx->esz), rows = up256((size_t)ctx->M * 4);
+    size_t part = gemm_partial_bytes(ctx->M, ctx->zdim, ctx->V, 1, ctx->st);
+    const size_t part2 = gemm_partial_bytes(ctx->V, ctx->zdim, ctx->M, 1, ctx->st);
+    if (part2 > part) part = part2;
+    part = up256(part);
+    if (logits + rows + part > BLSTM_NOALLOC_SCRATCH_BYTES)
+        return fail(BLSTM_ERR_WORKSPACE, "softmax_xent_fwd_bwd_noalloc: T*B = %d frames of V = %d classes need %zu bytes of scratch, "
+                    "the resident array holds %zu", ctx->M, ctx->V, logits + rows + part, (size_t)BLSTM_NOALLOC_SCRATCH_BYTES);
+    char* base = nullptr;
+    const int rc = resident_scratch(&base);
+    if (rc != BLSTM_OK) return rc;
+    SoftmaxScratch sc{base, reinterpret_cast<float*>(base + logits), reinterpret_cast<float*>(base + logits + rows),
+                      BLSTM_NOALLOC_SCRATCH_BYTES - logits - rows};
+    return softmax_xent_run(ctx, sc, theta, z, labels, loss_dev, dz, grad, static_cast<hipStream_t>(stream));
 }
 
 int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void* dz, float* grad, void* stream) {

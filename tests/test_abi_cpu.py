@@ -100,6 +100,19 @@ def test_calls_validate_before_launching():
         bl.blstm_destroy(ctx)
 
 
+def test_noalloc_entry_validates_and_rejects_oversized_shapes():
+    L = bl.lib()
+    small = bl.blstm_create(2, 2, 2, 2, 1, 0, 2, 0)
+    big = bl.blstm_create(21, 256, 260, 512, 4, 256, 32000, 1)          # 344 MB of logits: beyond the resident array
+    try:
+        assert L.softmax_xent_fwd_bwd_noalloc(small, None, None, None, None, None, None, None) == -1
+        assert L.softmax_xent_fwd_bwd_noalloc(small, 4100, 4096, 4096, 4096, 4096, 4096, None) == -4
+        assert L.softmax_xent_fwd_bwd_noalloc(big, 4096, 4096, 4096, 4096, 4096, 4096, None) == -3
+        assert "scratch" in bl.blstm_last_error()
+    finally:
+        bl.blstm_destroy(small); bl.blstm_destroy(big)
+
+
 def test_mix_validation():
     L = bl.lib()
     ptrs = (ctypes.c_void_p * 4)(4096, 8192, 12288, 16384)
