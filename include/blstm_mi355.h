@@ -162,11 +162,17 @@ int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
    chooses by shape: the second stream is used when each workgroup of the persistent recurrent kernel
    owns a single batch tile (the recurrence is then latency-bound and leaves the device underused). */
 #define BLSTM_OPT_OVERLAP 3
+/* BLSTM_OPT_TEST_ABORT (for tests of the failure path): 1 = the next blstm_forward raises the abort word of the
+   persistent kernels itself, as if one of their waits had been abandoned: every later wait returns at once, all
+   kernels run to their end, everything they write is NaN, and blstm_device_status reports BLSTM_ERR_HIP. */
+#define BLSTM_OPT_TEST_ABORT 4
 int blstm_set_option(blstm_ctx* ctx, int option, int value);
 
 /* The only call that synchronises: waits for `stream`, then reports whether a persistent kernel
    gave up a wait on another workgroup (BLSTM_ERR_HIP; the results of that step are invalid).
-   Returns 0 otherwise. */
+   Returns 0 otherwise.  The failure is also visible without this call: a wavefront that gave up a wait,
+   and every persistent launch after it until the next blstm_forward that follows a blstm_device_status,
+   adds NaN to what it writes, so the loss, the gradient and the updated weights of such a step are NaN. */
 int blstm_device_status(blstm_ctx* ctx, void* stream);
 
 /* bf16 <- RNE(master) over n elements (used once, to create the shadow of the initial weights). */

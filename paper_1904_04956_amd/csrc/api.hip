@@ -66,6 +66,7 @@ struct blstm_ctx {
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
+    bool test_abort;          // failure-handling tests: the next forward pass raises the abort word itself
     int overlap;              // weight-gradient products on a second stream beside the next layer's recurrence: 0 never, 1 always, 2 by shape
     hipStream_t side;         // created on first use
     hipEvent_t ev_fork, ev_da[2], ev_wg[2], ev_join, ev_fill;
@@ -285,7 +286,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
         c->wWP = w; w += up256((size_t)2 * 4 * H * c->Dp * 2);
     }
     // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
-    c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false;
+    c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false; c->test_abort = false;
     c->fwd_persistent.assign(c->L, 0);
     c->wUHT = w; c->wCNT = w; c->wHX = w; c->wDAX = w; c->hx_bytes = 0; c->dax_bytes = 0;
     if (c->st == DT_BF16 && rec_waves_for(c->H, c->B) > 0) {
@@ -426,9 +427,10 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
         if (ctx->rec_nbg > 0 && ctx->rec_path == 0) {   // all T frames of both directions in one launch
             unsigned* cnt = reinterpret_cast<unsigned*>(ctx->ws + ctx->wCNT);
             const int ncnt = 2 * ctx->rec_nbg * ctx->rec_tiles;
-            if (!ctx->abort_clean) {
-                RUN(PC_MISC, "abort word", launch_fill_u32(cnt + ncnt, 1, 0u, st));
+            if (!ctx->abort_clean || ctx->test_abort) {
+                RUN(PC_MISC, "abort word", launch_fill_u32(cnt + ncnt, 1, ctx->test_abort ? 1u : 0u, st));
                 ctx->abort_clean = true;
+                ctx->test_abort = false;
             }
             if (ctx->rec_sync == 0) RUN(PC_MISC, "counters", launch_fill_u32(cnt, ncnt, 0u, st));
             RecFwdArgs a{};
@@ -811,6 +813,7 @@ int blstm_set_option(blstm_ctx* c, int option, int value) {
     if (option == BLSTM_OPT_RECURRENT_PATH && (value == 0 || value == 1)) { c->rec_path = value; return BLSTM_OK; }
     if (option == BLSTM_OPT_RECURRENT_SYNC && (value == 0 || value == 1)) { c->rec_sync = value; return BLSTM_OK; }
     if (option == BLSTM_OPT_OVERLAP && value >= 0 && value <= 2) { c->overlap = value; return BLSTM_OK; }
+    if (option == BLSTM_OPT_TEST_ABORT && (value == 0 || value == 1)) { c->test_abort = value != 0; return BLSTM_OK; }
     return fail(BLSTM_ERR_DIM, "blstm_set_option: unknown option %d or value %d", option, value);
 }
 

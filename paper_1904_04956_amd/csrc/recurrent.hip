@@ -26,7 +26,9 @@
 //
 // Every wait is bounded by a wall-clock limit.  On expiry the wave raises a global abort word;
 // every later wait returns at once when it sees the word, so all waves run to the end of the
-// kernel (with invalid results, which blstm_device_status reports).
+// kernel.  A wave that abandoned a wait adds NaN to everything it writes from then on (h in the
+// forward kernel, dE/da in the backward one), so the failure travels in-band into the loss, the
+// gradient and the updated weights; blstm_device_status reports it as well.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -42,24 +44,27 @@ __device__ __forceinline__ f32x16_t mfma_bf16(const uint4& a, const uint4& b, f3
 __device__ __forceinline__ unsigned ld_coh_u32(const unsigned* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // ---- FENCED protocol ----------------------------------------------------------------------------
-// Waits until *cnt >= target; thread 0 polls.  One barrier inside.
-__device__ __forceinline__ void wait_counter(unsigned* cnt, unsigned target, unsigned* abort_word, unsigned long long limit_ticks) {
+// Waits until *cnt >= target; thread 0 polls.  One barrier inside.  Returns true (to every thread) if the
+// wait was abandoned.
+__device__ __forceinline__ bool wait_counter(unsigned* cnt, unsigned target, unsigned* abort_word, unsigned long long limit_ticks) {
+    int gave_up = 0;
     if (threadIdx.x == 0) {
         const unsigned long long t0 = wall_clock64();
         unsigned it = 0;
         while (ld_coh_u32(cnt) < target) {
             __builtin_amdgcn_s_sleep(1);
             if ((++it & 63u) == 0) {
-                if (ld_coh_u32(abort_word) != 0) break;
+                if (ld_coh_u32(abort_word) != 0) { gave_up = 1; break; }
                 if (wall_clock64() - t0 > limit_ticks) {
                     __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    gave_up = 1;
                     break;
                 }
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
-    __syncthreads();
+    return __syncthreads_or(gave_up) != 0;
 }
 // After the workgroup's stores: the barrier orders them before thread 0's agent-scope release.
 __device__ __forceinline__ void signal_counter(unsigned* cnt) {
@@ -288,6 +293,9 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     // they wait in registers until the next item has issued its loads of the exchanged h, and go out behind them.
     struct Tail { int t, b0; bool have, xok; float cn[EPT]; uint2 g[EPT]; uint2 hq; } tail;
     tail.have = false;
+    // NaN once this wave has abandoned a wait, or from the start if an earlier launch left the abort word raised:
+    // added to every h it writes
+    float poison = ld_coh_u32(a.abort_word) != 0 ? __builtin_nanf("") : 0.0f;
     auto flush_tail = [&]() __attribute__((always_inline)) {
         if (!tail.have) return;
         tail.have = false;
@@ -357,9 +365,9 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
                         load_chunks_cached<KSTEPS>(afrag, hp, valid);
                     }
                 }
-                ensure_written<KSTEPS>(afrag, hp, valid, gu, a.abort_word, a.limit_ticks);
+                if (ensure_written<KSTEPS>(afrag, hp, valid, gu, a.abort_word, a.limit_ticks)) poison = __builtin_nanf("");
             } else {
-                wait_counter(cnt + i, (unsigned)(NU * n), a.abort_word, a.limit_ticks);
+                if (wait_counter(cnt + i, (unsigned)(NU * n), a.abort_word, a.limit_ticks)) poison = __builtin_nanf("");
 #pragma unroll
                 for (int q = 0; q < KSTEPS; ++q)
                     afrag[q] = valid ? *reinterpret_cast<const uint4*>(hp + q * XPAIR) : make_uint4(0, 0, 0, 0);
@@ -429,7 +437,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
             gg[e] = fast_tanh(ax[e][2] + sum[e][2]);
             go[e] = fast_sigmoid(ax[e][3] + sum[e][3]);
             cn[e] = gf[e] * cp[e] + gi[e] * gg[e];
-            hn[e] = go[e] * fast_tanh(cn[e]);
+            hn[e] = go[e] * fast_tanh(cn[e]) + poison;
         }
         // A lane holds four rows of one unit; both copies of h want the units of a row side by side.  Regrouped
         // through LDS inside the wavefront (as dE/da in the backward kernel), every lane stores four units of one
@@ -563,6 +571,9 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     for (int e = 0; e < EPT; ++e) { dccarry[e] = 0.0f; ccarry[e] = 0.0f; }
     uint4 apre[MULTI ? 8 : 1];                           // first slab of the next item, loaded ahead (several tiles only)
     bool have_pre = false;
+    // NaN once this wave has abandoned a wait, or from the start if the abort word is already raised: added to
+    // every dE/da it writes
+    float poison = ld_coh_u32(a.abort_word) != 0 ? __builtin_nanf("") : 0.0f;
     auto do_item = [&](const int item, const Inputs& cur, Inputs& nxt) __attribute__((always_inline)) {
         const int ni = item / ntl, i = item - ni * ntl;
         const int n = T - 1 - ni;
@@ -625,8 +636,9 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
 #pragma unroll
                     for (int q = 0; q < 8; ++q) acc = mfma_bf16(afrag[sl & 1][q], bfrag[sl * 8 + q], acc);
                 }
+                if (gu) poison = __builtin_nanf("");
             } else {
-                wait_counter(cnt + i, (unsigned)(NU * (T - 1 - n)), a.abort_word, a.limit_ticks);
+                if (wait_counter(cnt + i, (unsigned)(NU * (T - 1 - n)), a.abort_word, a.limit_ticks)) poison = __builtin_nanf("");
 #pragma unroll
                 for (int q0 = 0; q0 < KSTEPS; q0 += 8) {
                     uint4 afrag[8];
@@ -671,7 +683,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         for (int e = 0; e < EPT; ++e) {
             const float gi = bf2f((bf16_t)(cur.g[e].x & 0xFFFFu)), gf = bf2f((bf16_t)(cur.g[e].x >> 16));
             const float gg = bf2f((bf16_t)(cur.g[e].y & 0xFFFFu)), go = bf2f((bf16_t)(cur.g[e].y >> 16));
-            const float dht = dh[e] + bf2f(cur.dy[e]);
+            const float dht = dh[e] + bf2f(cur.dy[e]) + poison;
             const float tc = fast_tanh(cthis[e]);
             const float dc = dht * go * (1.0f - tc * tc) + dcr[e];
             const float da_o = dht * tc * go * (1.0f - go);

@@ -175,6 +175,32 @@ def test_exchange_protocols_agree_bit_for_bit():
         lrn.close()
 
 
+def test_abandoned_wait_is_reported_in_band_and_recovered_from():
+    # The abort word is raised from the host (test option), so every wait of the persistent kernels returns at
+    # once and all kernels run to their end: the step's loss, z and gradient must be NaN (in-band), the status call
+    # must report the failure, and the next step must give the bits of a clean run.
+    from paper_1904_04956_amd import binding as bl
+    from paper_1904_04956_amd.harness import Learner
+    dims = dict(T=6, B=64, D=32, H=128, L=2, P=16, V=90)
+    dm, theta, x, labels = make_problem(dims, 1, 83, 2.0)
+    for sync in (1, 0):
+        lrn = Learner(mode=1, recurrent_sync=sync, **dims)
+        lrn.set_theta(theta); lrn.set_batch(x, labels)
+        lrn.calgrad(); lrn.check_status()
+        clean = (lrn.loss_value(), lrn.grad_numpy().copy(), lrn.z_numpy().copy())
+        assert np.isfinite(clean[0]) and np.all(np.isfinite(clean[1]))
+        bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_TEST_ABORT, 1)
+        lrn.calgrad()
+        with pytest.raises(bl.BlstmError) as e:
+            lrn.check_status()
+        assert e.value.code == -5 and "abandoned" in str(e.value)
+        assert np.isnan(lrn.loss_value()) and np.isnan(lrn.z_numpy()).any() and np.isnan(lrn.grad_numpy()).any()
+        lrn.calgrad(); lrn.check_status()                 # recovered: the word is cleared by the next forward pass
+        assert lrn.loss_value() == clean[0]
+        assert np.array_equal(lrn.grad_numpy(), clean[1]) and np.array_equal(lrn.z_numpy(), clean[2])
+        lrn.close()
+
+
 def test_persistent_and_stepwise_paths_agree():
     from paper_1904_04956_amd.harness import Learner
     dims = dict(T=7, B=70, D=48, H=256, L=2, P=32, V=150)
