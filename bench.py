@@ -78,7 +78,6 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel-class event pass")
     ap.add_argument("--rec-sync", type=int, default=-1, help="exchange protocol of the persistent kernels (library default if < 0)")
     ap.add_argument("--rec-path", type=int, default=0, help="1 = one launch per frame")
-    ap.add_argument("--overlap", type=int, default=-1, help="0 = weight-gradient products on the caller's stream")
     ap.add_argument("--mix-replicas", type=int, default=16, help="replicas of the separate adpsgd_mix measurement")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="first copy 1 GiB three times with a plain copy kernel (reference for HBM counters under rocprofv3 --pmc)")
@@ -112,8 +111,6 @@ def main():
     lrn = Learner(mode=w.mode, recurrent_path=args.rec_path, **d)
     if args.rec_sync >= 0:
         bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_RECURRENT_SYNC, args.rec_sync)
-    if args.overlap >= 0:
-        bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_OVERLAP, args.overlap)
     theta = inputs.make_theta(lrn.n, w.seed, bf16=bf)
     x, labels = inputs.make_batch(T, B, d["D"], d["V"], w.seed, bf16=bf)
     lrn.set_theta(theta)
@@ -128,6 +125,7 @@ def main():
         lrn.calgrad()
         lrn.apply(w.lr)
         bl.adpsgd_mix(masters, shadows, lrn.n, 2, [1, 0])
+        lrn.weights_changed()
 
     for _ in range(args.warmup):
         step()
@@ -161,7 +159,6 @@ def main():
     # (everything on one stream for this pass: events around a launch that shares the device with the
     #  second stream's products would time the sharing, not the kernel)
     if not args.no_profile:
-        bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_OVERLAP, 0)
         bl.blstm_profile_enable(lrn.ctx, 1)
         nprof = min(args.steps, 10)
         for _ in range(nprof):
@@ -169,7 +166,6 @@ def main():
         torch.cuda.synchronize()
         prof = bl.blstm_profile_read(lrn.ctx)
         bl.blstm_profile_enable(lrn.ctx, 0)
-        bl.blstm_set_option(lrn.ctx, bl.BLSTM_OPT_OVERLAP, args.overlap if args.overlap >= 0 else 2)
         fl = flops_by_class(T, B, d["D"], d["H"], d["L"], d["P"], d["V"])
         classes = {}
         for name, (ms, cnt) in prof.items():

@@ -15,8 +15,7 @@
  *   - Every pointer named theta, x, z, dz, grad, labels, loss, velocity or workspace is
  *     DEVICE memory owned by the caller.  The library never allocates or frees
  *     device memory and never synchronises the device: all work is enqueued on the
- *     caller's stream (a hipStream_t passed as void*, NULL = the null stream), or on a
- *     second stream of the context that is forked from and joined back to it inside a call.
+ *     caller's stream (a hipStream_t passed as void*, NULL = the null stream).
  *   - `partner` and every `*_out` size/offset argument is HOST memory.
  *   - Activations are time-major and row-major: [T][B][features].
  *   - mode 0: every tensor is float.  mode 1: theta, x, z, dz are bfloat16 (the
@@ -156,17 +155,19 @@ int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
    still holds the pattern (each element is its own ready flag: written once, so any other value is
    final whatever cache answered; elements that still show the pattern are re-read cache-bypassing). */
 #define BLSTM_OPT_RECURRENT_SYNC 2
-/* BLSTM_OPT_OVERLAP: 1 = blstm_backward runs the weight-gradient products on a second stream owned by
-   the context (default priority), forked from and joined to the caller's stream with events, so that
-   they overlap the next layer's recurrence; 0 keeps everything on the caller's stream; 2 (default)
-   chooses by shape: the second stream is used when each workgroup of the persistent recurrent kernel
-   owns a single batch tile (the recurrence is then latency-bound and leaves the device underused). */
-#define BLSTM_OPT_OVERLAP 3
+/* BLSTM_OPT_KEEP_WEIGHT_COPIES (default 0): the passes keep two private copies derived from theta in the workspace
+   (layer 0's W_x zero-padded to whole tiles, and U_h transposed for the backward recurrence).  0 = both are
+   rebuilt in every pass.  1 = they are kept from step to step for as long as blstm_forward / blstm_backward are
+   given the same theta pointer and the caller reports every change of the weights it points to (sgd_step,
+   adpsgd_mix, sgd_mix_pair, sync_average, a copy) with blstm_weights_changed before the next pass. */
+#define BLSTM_OPT_KEEP_WEIGHT_COPIES 3
 /* BLSTM_OPT_TEST_ABORT (for tests of the failure path): 1 = the next blstm_forward raises the abort word of the
    persistent kernels itself, as if one of their waits had been abandoned: every later wait returns at once, all
    kernels run to their end, everything they write is NaN, and blstm_device_status reports BLSTM_ERR_HIP. */
 #define BLSTM_OPT_TEST_ABORT 4
 int blstm_set_option(blstm_ctx* ctx, int option, int value);
+/* The weights behind theta have changed (see BLSTM_OPT_KEEP_WEIGHT_COPIES).  Host-side only, no device work. */
+int blstm_weights_changed(blstm_ctx* ctx);
 
 /* The only call that synchronises: waits for `stream`, then reports whether a persistent kernel
    gave up a wait on another workgroup (BLSTM_ERR_HIP; the results of that step are invalid).

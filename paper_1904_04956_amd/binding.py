@@ -21,7 +21,7 @@ EXPORTS = [
     "blstm_create", "blstm_destroy", "blstm_param_count", "blstm_workspace_bytes", "blstm_param_offset",
     "blstm_bind", "blstm_forward", "softmax_xent_fwd_bwd", "softmax_xent_fwd_bwd_noalloc", "blstm_backward", "sgd_step", "adpsgd_mix",
     "sgd_mix_pair", "sync_average", "blstm_lr_schedule",
-    "adpsgd_ring_partner", "blstm_shadow_refresh", "blstm_set_option", "blstm_device_status", "blstm_profile_enable", "blstm_profile_read",
+    "adpsgd_ring_partner", "blstm_shadow_refresh", "blstm_set_option", "blstm_weights_changed", "blstm_device_status", "blstm_profile_enable", "blstm_profile_read",
     "blstm_profile_classes", "blstm_profile_name", "blstm_last_error",
 ]
 
@@ -85,6 +85,8 @@ def lib():
     L.blstm_shadow_refresh.restype = c_int
     L.blstm_set_option.argtypes = [c_void_p, c_int, c_int]
     L.blstm_set_option.restype = c_int
+    L.blstm_weights_changed.argtypes = [c_void_p]
+    L.blstm_weights_changed.restype = c_int
     L.blstm_device_status.argtypes = [c_void_p, c_void_p]
     L.blstm_device_status.restype = c_int
     L.blstm_profile_enable.argtypes = [c_void_p, c_int]
@@ -224,13 +226,17 @@ def blstm_shadow_refresh(theta_master, theta_bf16, n, stream=None):
 
 BLSTM_OPT_RECURRENT_PATH = 1
 BLSTM_OPT_RECURRENT_SYNC = 2
-BLSTM_OPT_OVERLAP = 3
+BLSTM_OPT_KEEP_WEIGHT_COPIES = 3
 BLSTM_OPT_TEST_ABORT = 4
 BLSTM_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
 def blstm_set_option(ctx, option, value):
     return _check(lib().blstm_set_option(ctx, option, value))
+
+
+def blstm_weights_changed(ctx):
+    return _check(lib().blstm_weights_changed(ctx))
 
 
 def blstm_device_status(ctx, stream=None):

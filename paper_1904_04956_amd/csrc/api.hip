@@ -59,7 +59,8 @@ struct blstm_ctx {
     size_t off_wp, off_bp, off_ws, off_bs;
     // workspace (byte offsets)
     std::vector<size_t> wY, wG, wC;
-    size_t wAX, wPRE, wDA[2], wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, wPART2, wHX, wDAX, hx_bytes, dax_bytes, part_bytes, part2_bytes, ws_bytes;
+    std::vector<size_t> wDA;  // dE/da of every layer: all of them feed the weight-gradient products at the end of the backward pass
+    size_t wAX, wPRE, wDY[2], wDH, wDC, wLOGITS, wROWLOSS, wUHT, wCNT, wPART, wHX, wDAX, hx_bytes, dax_bytes, part_bytes, ws_bytes;
     int Dp;                   // 0, or the first layer's input width rounded up to whole tiles (padded copies of x and W_x)
     size_t wXP, wWP;
     int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
@@ -67,10 +68,9 @@ struct blstm_ctx {
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
     bool test_abort;          // failure-handling tests: the next forward pass raises the abort word itself
-    int overlap;              // weight-gradient products on a second stream beside the next layer's recurrence: 0 never, 1 always, 2 by shape
-    hipStream_t side;         // created on first use
-    hipEvent_t ev_fork, ev_da[2], ev_wg[2], ev_join, ev_fill;
-    bool side_ready;
+    bool keep_copies;         // the caller reports weight changes (blstm_weights_changed): derived copies are kept across steps
+    const void* wxp_of;       // the weights the padded W_x of layer 0 was made from (null: to be made), likewise the transposed U_h
+    const void* uht_of;
     char* ws;
     size_t ws_bound;
     bool have_forward;
@@ -130,20 +130,6 @@ GemmDesc gemm_desc(const blstm_ctx* c, DType in, DType out) {
     d.partial = reinterpret_cast<float*>(c->ws + c->wPART);
     d.partial_bytes = c->part_bytes;
     return d;
-}
-
-// The second stream and its events (host objects only), created at the first backward pass that uses them.
-hipError_t ensure_side(blstm_ctx* c) {
-    if (c->side_ready) return hipSuccess;
-    hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
-    if (e != hipSuccess) return e;
-    hipEvent_t* evs[7] = {&c->ev_fork, &c->ev_join, &c->ev_da[0], &c->ev_da[1], &c->ev_wg[0], &c->ev_wg[1], &c->ev_fill};
-    for (hipEvent_t* ev : evs) {
-        e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
-        if (e != hipSuccess) return e;
-    }
-    c->side_ready = true;
-    return hipSuccess;
 }
 
 inline const char* at(const void* base, size_t elems, size_t esz) { return static_cast<const char*>(base) + elems * esz; }
@@ -268,8 +254,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     }
     c->wAX = w;      w += up256(M * 8 * H * 4);
     c->wPRE = w;     w += up256(2 * B * 4 * H * 4);
-    c->wDA[0] = w;   w += up256(M * 8 * H * e);
-    c->wDA[1] = w;   w += up256(M * 8 * H * e);
+    for (int l = 0; l < c->L; ++l) { c->wDA.push_back(w); w += up256(M * 8 * H * e); }
     c->wDY[0] = w;   w += up256(M * 2 * H * e);
     c->wDY[1] = w;   w += up256(M * 2 * H * e);
     c->wDH = w;      w += up256(2 * B * H * 4);
@@ -318,15 +303,8 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
         upd(c->B, c->H, 4 * c->H, 2);                             // recurrent gradient of the step-by-step path
         c->wPART = w; c->part_bytes = up256(need);
         w += c->part_bytes;
-        // a second scratch for the weight-gradient products that run on the second stream
-        size_t need2 = 0;
-        auto upd2 = [&](int m, int n, int k, int batch) { size_t b = gemm_partial_bytes(m, n, k, batch, S); if (b > need2) need2 = b; };
-        if (c->P > 0) upd2(c->P, 2 * c->H, c->M, 1);
-        for (int l = 0; l < c->L; ++l) { upd2(4 * c->H, c->din(l), c->M, 2); upd2(4 * c->H, c->H, (c->T - 1) * c->B, 2); }
-        c->wPART2 = w; c->part2_bytes = up256(need2);
-        w += c->part2_bytes;
     }
-    c->overlap = 2; c->side = nullptr; c->side_ready = false;
+    c->keep_copies = false; c->wxp_of = nullptr; c->uht_of = nullptr;
     c->ws_bytes = w;
     c->ws = nullptr; c->ws_bound = 0; c->have_forward = false;
     c->prof = false; c->recs_used = 0;
@@ -338,11 +316,6 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
 
 void blstm_destroy(blstm_ctx* c) {
     if (!c) return;
-    if (c->side_ready) {
-        (void)hipStreamDestroy(c->side);
-        (void)hipEventDestroy(c->ev_fork); (void)hipEventDestroy(c->ev_join); (void)hipEventDestroy(c->ev_fill);
-        for (int i = 0; i < 2; ++i) { (void)hipEventDestroy(c->ev_da[i]); (void)hipEventDestroy(c->ev_wg[i]); }
-    }
     for (auto& r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete c;
 }
@@ -377,6 +350,7 @@ int blstm_bind(blstm_ctx* c, void* workspace, size_t bytes) {
     c->ws_bound = bytes;
     c->have_forward = false;
     c->abort_clean = false;
+    c->wxp_of = nullptr; c->uht_of = nullptr;
     return BLSTM_OK;
 }
 
@@ -414,7 +388,10 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
                     pa.src[1 + dd] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_wx[dd][0], e));
                     pa.dst[1 + dd] = WP + (size_t)dd * 4 * H * ctx->Dp; pa.ld[1 + dd] = Din; pa.rows[1 + dd] = 4 * H;
                 }
-                pa.count = 3; pa.cols = Din; pa.cols_p = ctx->Dp;
+                // (the copy of W_x is kept while the caller vouches for the weights: see blstm_weights_changed)
+                const bool have_wp = ctx->keep_copies && ctx->wxp_of == theta;
+                pa.count = have_wp ? 1 : 3; pa.cols = Din; pa.cols_p = ctx->Dp;
+                ctx->wxp_of = theta;
                 RUN(PC_MISC, "padded copies of x and W_x", launch_pad_cols(pa, st));
                 // (rows are Dp long for the weight gradient's whole tiles; the contraction needs whole slabs of 64 only)
                 d.seg[0] = GemmSeg{XP, WP, ctx->Dp, ctx->Dp, 0, (long long)4 * H * ctx->Dp, (Din + 63) / 64 * 64};
@@ -535,59 +512,40 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
     const DType S = ctx->st;
     float* DH = reinterpret_cast<float*>(ctx->ws + ctx->wDH);
     float* DC = reinterpret_cast<float*>(ctx->ws + ctx->wDC);
-    // Weight-gradient products only feed the gradient vector, so they run on a second stream beside
-    // the next layer's (latency-bound) recurrence: fork after each layer's dE/da is complete, join at
-    // the end.  dE/da alternates between two buffers so that a layer's products can still read theirs
-    // while the next layer writes the other.
-    // By shape: the second stream pays while the recurrence is latency-bound (one batch tile per
-    // workgroup); with several tiles per workgroup it is throughput-bound and the two only compete.
-    const bool ov = ctx->overlap == 1 || (ctx->overlap == 2 && ctx->rec_nbg > 0 && ctx->rec_path == 0 && ctx->rec_tiles <= 1);
-    hipStream_t ws = st;                                 // stream of the weight-gradient products
-    if (ov) {
-        HIPCHK("second stream", ensure_side(ctx));
-        ws = ctx->side;
-        HIPCHK("fork", hipEventRecord(ctx->ev_fork, st));
-        HIPCHK("fork", hipStreamWaitEvent(ws, ctx->ev_fork, 0));
-    }
-    auto wgrad_desc = [&](DType out) {
-        GemmDesc d = gemm_desc(ctx, S, out);
-        if (ov) { d.partial = reinterpret_cast<float*>(ctx->ws + ctx->wPART2); d.partial_bytes = ctx->part2_bytes; }
-        return d;
-    };
-    bool wg_pending[2] = {false, false};
+    // The weight-gradient products only feed the gradient vector and depend on nothing but each layer's dE/da, so
+    // they are collected here and run as one grouped launch at the end (every layer keeps its own dE/da buffer): one
+    // by one most of them have too few tiles for the device, together they fill it.  (Running a layer's products on
+    // a second stream beside the next layer's recurrence was measured and dropped: sharing the CUs slows the
+    // recurrence, a chain of latencies, by more than the products gain.)
+    std::vector<GemmDesc> wgrads;
+    wgrads.reserve(2 * ctx->L + 1);
     bool persistent = false;                            // some layer's forward pass ran the persistent kernel
     for (int l = 0; l < ctx->L; ++l) persistent = persistent || ctx->fwd_persistent[l] != 0;
     const bool sentinel = persistent && ctx->rec_sync == 1;
-    if (persistent) {                                    // U_h^T of every layer and direction in one launch
+    if (persistent && !(ctx->keep_copies && ctx->uht_of == theta)) {   // U_h^T of every layer and direction in one launch
         TransposeUhArgs ta{};
         for (int l = 0; l < ctx->L; ++l)
             for (int d = 0; d < 2; ++d)
                 ta.src[2 * l + d] = reinterpret_cast<const unsigned short*>(at(theta, ctx->off_uh[d][l], e));
         ta.dst = reinterpret_cast<unsigned short*>(ctx->ws + ctx->wUHT);
         ta.count = 2 * ctx->L;
-        // (on the stream of the weight-gradient products when there is one: the first recurrence waits for that
-        // stream's sentinel fill anyway, and the bottleneck's input gradient runs on `st` meanwhile)
-        if (ov && sentinel) RUN_ON(ws, PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, ws));
-        else RUN(PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, st));
+        RUN(PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, st));
+        ctx->uht_of = theta;
     }
-    // In sentinel mode every layer's exchange copy of dE/da starts as "not written yet": one fill,
-    // on the stream of the weight-gradient products so that it runs beside the products at the top.
-    bool fill_pending = false;
-    if (sentinel) {
-        RUN_ON(ws, PC_MISC, "sentinel fill of da", launch_fill_bytes16(ctx->ws + ctx->wDAX, ctx->dax_bytes * ctx->L, 0xFFFFFFFFu, ws));
-        if (ov) { HIPCHK("fork", hipEventRecord(ctx->ev_fill, ws)); fill_pending = true; }
-    }
+    // In sentinel mode every layer's exchange copy of dE/da starts as "not written yet": one fill.
+    if (sentinel)
+        RUN(PC_MISC, "sentinel fill of da", launch_fill_bytes16(ctx->ws + ctx->wDAX, ctx->dax_bytes * ctx->L, 0xFFFFFFFFu, st));
     const char* dY;
     int next_buf = 0;
     if (P > 0) {
         const char* YL = ctx->ws + ctx->wY[ctx->L - 1];
         {   // dW_p = dz^T y
-            GemmDesc d = wgrad_desc(DT_F32);
+            GemmDesc d = gemm_desc(ctx, S, DT_F32);
             d.M = P; d.N = 2 * H; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{dz, YL, P, 2 * H, 0, 0, M};
             d.C = grad + ctx->off_wp; d.ldc = 2 * H;
             d.rowsum = grad + ctx->off_bp;             // db_p = sum over frames of dz
-            RUN_ON(ws, PC_GEMM_WGRAD, "dW_p", launch_gemm(d, ws));
+            wgrads.push_back(d);
         }
         {   // dy = dz W_p
             GemmDesc d = gemm_desc(ctx, S, S);
@@ -607,16 +565,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
         const char* Y = ctx->ws + ctx->wY[l];
         const char* G = ctx->ws + ctx->wG[l];
         const float* C = reinterpret_cast<const float*>(ctx->ws + ctx->wC[l]);
-        const int db = l & 1;
-        char* DA = ctx->ws + ctx->wDA[db];
-        if (ov && wg_pending[db]) {                      // the products of layer l+2 still read this buffer
-            HIPCHK("buffer reuse", hipStreamWaitEvent(st, ctx->ev_wg[db], 0));
-            wg_pending[db] = false;
-        }
-        if (fill_pending) {
-            HIPCHK("fill", hipStreamWaitEvent(st, ctx->ev_fill, 0));
-            fill_pending = false;
-        }
+        char* DA = ctx->ws + ctx->wDA[l];
         // The layer's backward recurrence takes the path its forward recurrence took: the two persistent
         // kernels share the order of the saved gates, the per-frame kernels theirs.
         bool rec_done = false;
@@ -664,12 +613,10 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
                 RUN(PC_GEMM_REC_BWD, "recurrent gradient", launch_gemm(d, st));
             }
         }
-        if (ov) {                                        // dE/da of this layer is complete: fork
-            HIPCHK("fork", hipEventRecord(ctx->ev_da[db], st));
-            HIPCHK("fork", hipStreamWaitEvent(ws, ctx->ev_da[db], 0));
-        }
+        GemmDesc lw[2];
         {   // dW_x = da^T x, both directions
-            GemmDesc d = wgrad_desc(DT_F32);
+            GemmDesc& d = lw[0];
+            d = gemm_desc(ctx, S, DT_F32);
             d.batch = 2; d.M = 4 * H; d.N = Din; d.atrans = true; d.btrans = true;
             d.seg[0] = GemmSeg{DA, Xin, 8 * H, Din, 4 * H, 0, M};
             if (l == 0 && ctx->Dp > 0) {                 // the forward pass's padded x: whole tiles of columns, N of them stored
@@ -679,10 +626,10 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             d.C = grad + ctx->off_wx[0][l]; d.ldc = Din; d.sC = (long long)(ctx->off_wx[1][l] - ctx->off_wx[0][l]);
             d.rowsum = grad + ctx->off_b[0][l];        // db = sum over frames of da
             d.sRowsum = (long long)(ctx->off_b[1][l] - ctx->off_b[0][l]);
-            RUN_ON(ws, PC_GEMM_WGRAD, "dW_x", launch_gemm(d, ws));
         }
-        {   // dU_h = da^T h_prev: forward direction pairs da[t] with h[t-1], backward direction with h[t+1]
-            GemmDesc d = wgrad_desc(DT_F32);
+        {   // dU_h = da^T h_prev: forward direction pairs da[t] with h[t-1], backward direction with h[t+1] (T = 1: an empty sum)
+            GemmDesc& d = lw[1];
+            d = gemm_desc(ctx, S, DT_F32);
             d.batch = 2; d.M = 4 * H; d.N = H; d.atrans = true; d.btrans = true;
             const char* A0 = DA + ((size_t)B * 8 * H) * e;
             const char* A1 = DA + ((size_t)4 * H) * e;
@@ -690,8 +637,8 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             const char* B1 = Y + ((size_t)B * 2 * H + H) * e;
             d.seg[0] = GemmSeg{A0, B0, 8 * H, 2 * H, (long long)((A1 - A0) / (long long)e), (long long)((B1 - B0) / (long long)e), (T - 1) * B};
             d.C = grad + ctx->off_uh[0][l]; d.ldc = H; d.sC = (long long)(ctx->off_uh[1][l] - ctx->off_uh[0][l]);
-            RUN_ON(ws, PC_GEMM_WGRAD, "dU_h", launch_gemm(d, ws));
         }
+        wgrads.push_back(lw[0]); wgrads.push_back(lw[1]);
         if (l > 0) {   // dx = da_fwd W_x_fwd + da_bwd W_x_bwd, the gradient of the layer below's output
             GemmDesc d = gemm_desc(ctx, S, S);
             d.M = M; d.N = Din; d.btrans = true; d.nseg = 2;
@@ -702,15 +649,8 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             dY = ctx->ws + ctx->wDY[next_buf];
             next_buf ^= 1;
         }
-        if (ov) {
-            HIPCHK("fork", hipEventRecord(ctx->ev_wg[db], ws));
-            wg_pending[db] = true;
-        }
     }
-    if (ov) {                                            // join: everything on the second stream precedes what follows on st
-        HIPCHK("join", hipEventRecord(ctx->ev_join, ws));
-        HIPCHK("join", hipStreamWaitEvent(st, ctx->ev_join, 0));
-    }
+    RUN(PC_GEMM_WGRAD, "weight gradients", launch_gemm_group(wgrads.data(), (int)wgrads.size(), st));
     return BLSTM_OK;
 }
 
@@ -812,9 +752,18 @@ int blstm_set_option(blstm_ctx* c, int option, int value) {
     if (!c) return fail(BLSTM_ERR_NULL, "blstm_set_option: null argument");
     if (option == BLSTM_OPT_RECURRENT_PATH && (value == 0 || value == 1)) { c->rec_path = value; return BLSTM_OK; }
     if (option == BLSTM_OPT_RECURRENT_SYNC && (value == 0 || value == 1)) { c->rec_sync = value; return BLSTM_OK; }
-    if (option == BLSTM_OPT_OVERLAP && value >= 0 && value <= 2) { c->overlap = value; return BLSTM_OK; }
+    if (option == BLSTM_OPT_KEEP_WEIGHT_COPIES && (value == 0 || value == 1)) {
+        c->keep_copies = value != 0; c->wxp_of = nullptr; c->uht_of = nullptr;
+        return BLSTM_OK;
+    }
     if (option == BLSTM_OPT_TEST_ABORT && (value == 0 || value == 1)) { c->test_abort = value != 0; return BLSTM_OK; }
     return fail(BLSTM_ERR_DIM, "blstm_set_option: unknown option %d or value %d", option, value);
+}
+
+int blstm_weights_changed(blstm_ctx* c) {
+    if (!c) return fail(BLSTM_ERR_NULL, "blstm_weights_changed: null argument");
+    c->wxp_of = nullptr; c->uht_of = nullptr;
+    return BLSTM_OK;
 }
 
 int blstm_device_status(blstm_ctx* c, void* stream) {

@@ -1,20 +1,29 @@
 // C(m,n) = sum_k A(m,k) B(n,k) (+ bias[n]) (+ add[m][n]) on the matrix cores of gfx950.
 //
-// One workgroup of four wavefronts (2 x 2) owns a (64 TM) x (64 TN) tile of C; each wavefront
-// owns a (32 TM) x (32 TN) part as TM x TN MFMA 32x32 accumulators.  Two tile shapes are built:
-// 256x256 (TM = TN = 4: each LDS fragment feeds four products, which keeps LDS traffic at half
-// of its bandwidth when the matrix cores are busy) for the large products, and 128x128 for
-// products whose output has too few large tiles to fill 256 compute units.  A K-slab of eight
-// 16-byte chunks per row (64 bf16 or 32 float) is staged through LDS, double buffered, with the
-// next slab's global loads in flight while the current one is multiplied, and the fragments of
-// the next sub-step read from LDS while the current products issue.  Operands whose contraction
-// index is the slow one in memory ("transposed") are loaded along their fast index, so all three
-// forms of a training step's products (X W^T, dA W, dA^T X) run through the same inner loop:
-// 16-bit ones of full tiles stay in LDS as they lie in memory and are transposed by the LDS read
-// itself (ds_read_b64_tr_b16); the others are transposed in registers on the way to LDS.  LDS
-// rows are XOR-swizzled at chunk granularity so that both the stores and the MFMA fragment reads
-// spread over the banks.  Products with a small output and a long contraction are split along K over
-// blockIdx.y into float partial tiles that a second kernel sums in a fixed order.
+// A workgroup of 2 x WN wavefronts owns a (64 TM) x (32 TN WN) tile of C; each wavefront owns a
+// (32 TM) x (32 TN) part as TM x TN MFMA 32x32 accumulators.  A K-slab of eight 16-byte chunks per
+// row (64 bf16 or 32 float) lives in LDS, rows XOR-swizzled at chunk granularity so that loads,
+// stores and the MFMA fragment reads all spread over the banks.  Operands whose contraction index
+// is the slow one in memory ("transposed") are loaded along their fast index, so all three forms
+// of a training step's products (X W^T, dA W, dA^T X) run through the same inner loop: 16-bit ones
+// of full tiles lie in LDS as they lie in memory and are transposed by the LDS read itself
+// (ds_read_b64_tr_b16); the others are transposed in registers on the way to LDS.
+//
+// Two ways of bringing a slab into LDS:
+//   direct   bf16 operands, whole tiles, aligned: global_load_lds_dwordx4 writes the slab straight
+//            into LDS in the swizzled layout (each lane fetches the chunk that belongs at its LDS
+//            slot).  Tiles: 256x128 on four wavefronts with ONE LDS buffer, a slab's fragments all
+//            read into registers before the next slab's loads overwrite it, two workgroups per CU
+//            taking turns on the matrix cores (the workhorse: 3/4 of the operand bytes of 128x128
+//            per flop, and the vector-memory path of a CU, about 45 bytes per clock from L2, is what
+//            bounds these products); 128x128 with a ring of two or three buffers for products with
+//            too few large tiles; 256x256 on eight wavefronts for a handful of tiles with a very
+//            long contraction.
+//   staged   every other case (float operands, ragged shapes, unaligned rows): global loads into
+//            registers two or four slabs ahead, LDS stores, double-buffered LDS.
+// Products with a small output and a long contraction are split along K over blockIdx.y into float
+// partial tiles that a second kernel sums in a fixed order.  Several independent products of one
+// form can share one launch (gemm_group_kernel).
 #include "common.hpp"
 #include "gemm.hpp"
 
@@ -256,8 +265,19 @@ __device__ __forceinline__ void mma(f32x16_t& acc, const uint4& a, const uint4& 
 // D = sets of staging registers = slabs the global loads run ahead.  Two leaves room for two workgroups per
 // CU; four is for launches with at most one workgroup per CU, which have nothing else to cover the
 // latency of their loads with and the whole register file to themselves.
-template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D>
-__global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P) {
+// NS = 0: slabs are staged through registers as described above (any element type, guarded or not).
+// NS >= 1: direct mode, for 16-bit operands in the unguarded form.  The slabs go from global memory straight into LDS
+// (global_load_lds_dwordx4: lane l of a wavefront writes its 16 bytes at the wave-uniform LDS address in M0 plus
+// 16 l), in the same swizzled layouts the fragment reads expect: no staging registers, no LDS stores, no transposes
+// in registers.  These loads are written in assembly and waited for with explicit vmcnt counts; the compiler does
+// not see them.  NS >= 2: a ring of NS LDS buffers, the loads of slab it + NS - 1 issued at the top of iteration it,
+// one barrier per slab.  NS = 1: one LDS buffer; all fragments of a slab are read into registers, a barrier frees the
+// buffer for the next slab's loads, and the products run from registers while those loads are in flight; workgroups
+// sharing a CU take turns on the matrix cores (one multiplies while another reads its fragments).
+// `lin`, `split`, `z`: tile index within the product, K range and batch index of this workgroup.
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D, int NS>
+__device__ __forceinline__ void gemm_tile(const Params& P, int lin, const int split, const int z) {
+    static_assert(NS == 0 || (FAST && sizeof(TI) == 2 && D == 2), "direct mode is built for the unguarded 16-bit form");
     static_assert(D == 2 || (D == 4 && FAST && WN == 2), "the deep pipeline exists for the unguarded 128x128 tile only");
     static_assert(WN == 2 || (FAST && !RS), "the eight-wave shape exists in the unguarded form only");
     constexpr int NT = 128 * WN;                        // threads: 2 x WN wavefronts
@@ -278,7 +298,6 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
     // range of tiles so that its L2 sees neighbouring tiles, then walk the range in bands
     // of eight tile rows so that concurrently resident tiles share A rows and B columns.
     const int nt = P.ntm * P.ntn;
-    int lin = blockIdx.x;
     {
         const int nt8 = nt & ~7;
         if (lin < nt8) lin = (lin & 7) * (nt8 >> 3) + (lin >> 3);
@@ -289,8 +308,6 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
     const int tm = first_m + (lin % band) % bh;
     const int tn = (lin % band) / bh;
     const int row0 = tm * BM, col0 = tn * BN;
-    const int z = blockIdx.z;
-    const int split = blockIdx.y;
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -371,7 +388,7 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
     // fragment reads of each 32-row block (lane group g = lane / 16: rows 16 (g & 1) .., k-rows 8 (g / 2) ..)
     constexpr bool TRP = FAST && sizeof(TI) == 2;
     constexpr int CPR_A = BM / 8, CPR_B = BN / 8;
-    static_assert(!TRP || (NT / CPR_A == 16 && NT / CPR_B == 16), "a pass of loads covers sixteen k-rows");
+    static_assert(NS > 0 || !TRP || (NT / CPR_A == 16 && NT / CPR_B == 16), "a pass of loads covers sixteen k-rows");
     auto tr_soff = [&](int cpr) { const int kt = tid / cpr, mc = tid % cpr; return kt * cpr + ((((mc >> 1) ^ ((kt & 3) << 1)) << 1) | (mc & 1)); };
     const int soff_ta = tr_soff(CPR_A), soff_tb = tr_soff(CPR_B);
     const uint32_t voff_ta = (uint32_t)((tid / CPR_A) * a0.ld * ES + (tid % CPR_A) * 16);
@@ -387,6 +404,133 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
             troff_b[j] = (8 * (g >> 1) + (li >> 2)) * (BN * 2) + (((wn * 2 * TN + 2 * j + (g & 1)) ^ sw) << 5) + (li & 3) * 8;
     }
 
+    // (rows 32 apart: the swizzle flips bit 2 of the chunk column, which is the offset of sub-step q ^ 2)
+    auto lfrag = [&](const uint4* a_s, const uint4* b_s, int q, uint4 (&af)[TM], uint4 (&bf)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if constexpr (AT && TRP) af[i] = lfrag_tr<BM * 2>(reinterpret_cast<const char*>(a_s) + troff_a[i], 16 * q);
+            else af[i] = a_s[roff_a[(i & 1) ? (q ^ 2) : q] + i * 32 * CHUNKS];
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if constexpr (BT && TRP) bf[j] = lfrag_tr<BN * 2>(reinterpret_cast<const char*>(b_s) + troff_b[j], 16 * q);
+            else bf[j] = b_s[roff_b[(j & 1) ? (q ^ 2) : q] + j * 32 * CHUNKS];
+        }
+    };
+
+    const int nslab = it_end - it_begin;
+    if constexpr (NS > 0) {
+        // ---- direct mode ----------------------------------------------------------------------------------------
+        constexpr int NWV = 2 * WN;                         // wavefronts
+        constexpr int NIA = BM * 8 / 64 / NWV, NIB = BN * 8 / 64 / NWV;   // load instructions per wavefront, slab and operand
+        const int wv = __builtin_amdgcn_readfirstlane(wave);
+        const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
+        // Instruction j of wavefront wv fills the 64 LDS words (16 bytes each) starting at word 64 (j NWV + wv) of its
+        // operand's buffer; lane l fetches the chunk that belongs at word 64 (j NWV + wv) + l in the swizzled layout.
+        unsigned voa[NIA], vob[NIB];
+#pragma unroll
+        for (int j = 0; j < NIA; ++j) {
+            const int jj = j * NWV + wv;
+            if constexpr (AT) {
+                const int kt = (64 / CPR_A) * jj + lane / CPR_A, pos = lane % CPR_A;
+                const int mc = ((((pos >> 1) ^ ((kt & 3) << 1))) << 1) | (pos & 1);
+                voa[j] = (unsigned)(kt * a0.ld * ES + mc * 16);
+            } else {
+                const int r = 8 * jj + (lane >> 3);
+                voa[j] = (unsigned)(r * a0.ld * ES + (((lane & 7) ^ swz(r)) << 4));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NIB; ++j) {
+            const int jj = j * NWV + wv;
+            if constexpr (BT) {
+                const int kt = (64 / CPR_B) * jj + lane / CPR_B, pos = lane % CPR_B;
+                const int mc = ((((pos >> 1) ^ ((kt & 3) << 1))) << 1) | (pos & 1);
+                vob[j] = (unsigned)(kt * b0.ld * ES + mc * 16);
+            } else {
+                const int r = 8 * jj + (lane >> 3);
+                vob[j] = (unsigned)(r * b0.ld * ES + (((lane & 7) ^ swz(r)) << 4));
+            }
+        }
+        auto dma = [](unsigned lds_addr, const char* gbase, unsigned voff) __attribute__((always_inline)) {
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(lds_addr), "v"(voff), "s"(gbase) : "memory");
+        };
+        auto issue = [&](int it) __attribute__((always_inline)) {
+            const bool s2 = it >= ntiles[0];
+            const int k0 = (it - (s2 ? ntiles[0] : 0)) * BK;
+            const char* pa = static_cast<const char*>(s2 ? a1.p : a0.p);
+            const char* pb = static_cast<const char*>(s2 ? b1.p : b0.p);
+            const long long lda = a0.ld, ldb = b0.ld;      // (both segments share their leading dimensions in the unguarded form)
+            pa += AT ? ((long long)k0 * lda + row0) * ES : ((long long)row0 * lda + k0) * ES;
+            pb += BT ? ((long long)k0 * ldb + col0) * ES : ((long long)col0 * ldb + k0) * ES;
+            const unsigned sb = lds0 + (unsigned)(((it - it_begin) % NS) * STAGE * 16);
+#pragma unroll
+            for (int j = 0; j < NIA; ++j) dma(sb + (unsigned)((j * NWV + wv) * 1024), pa, voa[j]);
+#pragma unroll
+            for (int j = 0; j < NIB; ++j) dma(sb + (unsigned)(BM * 128 + (j * NWV + wv) * 1024), pb, vob[j]);
+        };
+        if constexpr (NS == 1) {
+            // One LDS buffer: a slab's fragments are all read into registers, a barrier frees the buffer for the next
+            // slab's loads, and the products run from registers while those loads are in flight.  Two workgroups per
+            // CU take turns on the matrix cores: one multiplies while the other reads its fragments.
+            uint4 fa[CHUNKS / 2][TM], fb[CHUNKS / 2][TN];
+            if (nslab > 0) issue(it_begin);
+            for (int it = it_begin; it < it_end; ++it) {
+                asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+                for (int q = 0; q < CHUNKS / 2; ++q) lfrag(smem, smem + BM * CHUNKS, q, fa[q], fb[q]);
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                if (it + 1 < it_end) issue(it + 1);
+#pragma unroll
+                for (int q = 0; q < CHUNKS / 2; ++q) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) mma<TI>(acc[i][j], fa[q][i], fb[q][j]);
+                    if (RS && do_rs && it < ntiles[0]) {
+#pragma unroll
+                        for (int i = 0; i < NRS; ++i) rs[i] = add_row(rs[i], fa[q][i]);
+                    }
+                }
+            }
+            __syncthreads();
+        } else {
+#pragma unroll
+        for (int u = 0; u < NS - 1; ++u)
+            if (nslab > u) issue(it_begin + u);
+        for (int it = it_begin; it < it_end; ++it) {
+            // this wavefront's loads of slab `it` have landed when at most the loads of the younger slabs are outstanding
+            if constexpr (NS == 2) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+            else {
+                const int younger = min(NS - 2, it_end - 1 - it);
+                if (younger == 0) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+                else if (younger == 1) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(NIA + NIB) : "memory");
+                else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(2 * (NIA + NIB)) : "memory");
+            }
+            // (behind the barrier every wavefront has finished the products of slab it - 1, whose buffer the next loads overwrite)
+            if (it + NS - 1 < it_end) issue(it + NS - 1);
+            const uint4* a_s = smem + ((it - it_begin) % NS) * STAGE;
+            const uint4* b_s = a_s + BM * CHUNKS;
+            constexpr int NF = (TM * TN <= 4) ? 2 : 1;
+            uint4 af[NF][TM], bf[NF][TN];
+            if (NF == 2) lfrag(a_s, b_s, 0, af[0], bf[0]);
+#pragma unroll
+            for (int q = 0; q < CHUNKS / 2; ++q) {
+                if (NF == 2) { if (q + 1 < CHUNKS / 2) lfrag(a_s, b_s, q + 1, af[(q + 1) % NF], bf[(q + 1) % NF]); }
+                else lfrag(a_s, b_s, q, af[0], bf[0]);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) mma<TI>(acc[i][j], af[q % NF][i], bf[q % NF][j]);
+                if (RS && do_rs && it < ntiles[0]) {
+#pragma unroll
+                    for (int i = 0; i < NRS; ++i) rs[i] = add_row(rs[i], af[q % NF][i]);
+                }
+            }
+        }
+        __syncthreads();                                    // the epilogue reuses the buffers
+        }
+    } else {
     // D sets of staging registers: the loads of slab it + D are issued while slab it is multiplied and
     // slabs it + 1 .. it + D - 1 (loaded in earlier iterations) wait in the other sets for their LDS buffer.
     uint4 ra[D][NCA], rb[D][NCB];
@@ -424,21 +568,6 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
         else if constexpr (BT) sstore_rowfast_off<TI, NCB, PR>(b_s, rb, soff_r);
         else sstore_kfast_off<NCB, RP>(b_s, rb, soff_k);
     };
-    // (rows 32 apart: the swizzle flips bit 2 of the chunk column, which is the offset of sub-step q ^ 2)
-    auto lfrag = [&](const uint4* a_s, const uint4* b_s, int q, uint4 (&af)[TM], uint4 (&bf)[TN]) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if constexpr (AT && TRP) af[i] = lfrag_tr<BM * 2>(reinterpret_cast<const char*>(a_s) + troff_a[i], 16 * q);
-            else af[i] = a_s[roff_a[(i & 1) ? (q ^ 2) : q] + i * 32 * CHUNKS];
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            if constexpr (BT && TRP) bf[j] = lfrag_tr<BN * 2>(reinterpret_cast<const char*>(b_s) + troff_b[j], 16 * q);
-            else bf[j] = b_s[roff_b[(j & 1) ? (q ^ 2) : q] + j * 32 * CHUNKS];
-        }
-    };
-
-    const int nslab = it_end - it_begin;
     if (nslab > 0) {
         gload(it_begin, ra[0], rb[0]);
         sstore(0, ra[0], rb[0]);
@@ -488,6 +617,8 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
             if (it + u < it_end) step(it + u, false, ra[u], rb[u], ra[(u + 1) % D], rb[(u + 1) % D]);
     }
 
+    }
+
     if (RS && do_rs) {
         float* out = P.splits > 1 ? P.rs_partial + ((long long)z * P.splits + split) * P.M : P.rowsum + z * P.sRowsum;
 #pragma unroll
@@ -511,8 +642,9 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
             float* part = to_part ? P.partial + ((long long)z * P.splits + split) * (long long)P.M * P.N : nullptr;
             TO* Cz = static_cast<TO*>(P.C) + z * P.sC;
             const TI* bz = (!to_part && P.bias) ? static_cast<const TI*>(P.bias) + z * P.sBias : nullptr;
-            constexpr int RR = 128;                         // tile rows per round: RR x BN floats fill the LDS
-            static_assert(RR * BN * 4 <= 2 * STAGE * 16, "a round of the staged epilogue must fit the LDS of the main loop");
+            constexpr int LDSB = (NS > 0 ? NS : 2) * STAGE * 16;
+            constexpr int RR = 128 * BN * 4 <= LDSB ? 128 : 64;   // tile rows per round: RR x BN floats fit the LDS of the main loop
+            static_assert(RR * BN * 4 <= LDSB, "a round of the staged epilogue must fit the LDS of the main loop");
             constexpr int GPR = BN / 4, RPP = NT / GPR;     // 16-byte groups per row, rows per pass of the stores
 #pragma unroll
             for (int h = 0; h < BM / RR; ++h) {
@@ -594,6 +726,37 @@ __global__ __launch_bounds__(128 * WN, D == 2 ? 2 : 1) void gemm_kernel(Params P
         }
 }
 
+// Workgroups per CU the launch bounds allow for: by LDS in the ring modes, by registers with one buffer.
+template <int TM, int TN, int WN, int D, int NS>
+constexpr int occupancy_target() {
+    if (NS == 1) return TM * TN <= 4 ? 3 : 2;
+    if (NS > 1) return NS * (64 * TM + 32 * TN * WN) * 128 <= 80 * 1024 ? 2 : 1;
+    return D == 2 ? 2 : 1;
+}
+
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D, int NS>
+__global__ __launch_bounds__(128 * WN, (occupancy_target<TM, TN, WN, D, NS>())) void gemm_kernel(Params P) {
+    gemm_tile<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D, NS>(P, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
+}
+
+// Several independent products of one form in one launch (the weight gradients of all layers): workgroup x belongs
+// to the product g with first[g] <= x < first[g + 1]; within it, tiles are numbered batch-major.  No split along K.
+constexpr int GROUP_MAX = 12;
+struct GroupParams {
+    Params p[GROUP_MAX];
+    int first[GROUP_MAX + 1];
+    int n;
+};
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D, int NS>
+__global__ __launch_bounds__(128 * WN, (occupancy_target<TM, TN, WN, D, NS>())) void gemm_group_kernel(GroupParams G) {
+    const int x = (int)blockIdx.x;
+    int g = 0;
+    for (int k = 1; k < G.n; ++k) if (x >= G.first[k]) g = k;
+    const Params& P = G.p[g];
+    const int local = x - G.first[g], per = P.ntm * P.ntn;
+    gemm_tile<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D, NS>(P, local % per, 0, local / per);
+}
+
 // C[m][n] = sum over splits of partial[z][s][m][n] (+ bias[n]) in the order s = 0, 1, ...
 template <typename TI, typename TO>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M, int N,
@@ -656,20 +819,25 @@ int fast_flags(const void* p, long long ld, long long stride, int batch, bool ro
     return f;
 }
 
-template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D = 2>
+template <typename K>
+hipError_t allow_lds(K kernel, size_t lds, bool* done) {
+    if (*done || lds <= 48 * 1024) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) *done = true;
+    return e;
+}
+
+template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D = 2, int NS = 0>
 hipError_t launch_kernel(const Params& P, dim3 grid, hipStream_t stream) {
-    constexpr size_t lds = 2 * (size_t)(64 * TM + 32 * TN * WN) * CHUNKS * 16;
+    constexpr size_t lds = (NS > 0 ? NS : 2) * (size_t)(64 * TM + 32 * TN * WN) * CHUNKS * 16;
     static thread_local bool attr_set = false;
-    if (!attr_set && lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL((gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D>), grid, dim3(128 * WN), lds, stream, P);
+    hipError_t e = allow_lds(&gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D, NS>, lds, &attr_set);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((gemm_kernel<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D, NS>), grid, dim3(128 * WN), lds, stream, P);
     return hipGetLastError();
 }
 
+// ---- register-staged kernels: float operands, guarded shapes, the A^T B^T... forms the direct mode does not build ----
 template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN>
 hipError_t launch_shape(const Params& P, bool fast, bool deep, dim3 grid, hipStream_t stream) {
     if constexpr (WN != 2) {
@@ -700,13 +868,44 @@ hipError_t launch_form(const GemmDesc& d, const Params& P, bool fast, bool deep,
     return launch_shape<TI, TO, true, false, TM, TN, WN>(P, fast, deep, grid, stream);
 }
 
+// ---- direct-mode kernels: bf16 operands, unguarded, forms X W^T, dA W and dA^T X -------------------------------
+// variant 0: 128x128 tile, two LDS buffers, two workgroups per CU; 1: 128x128, three buffers (launches of at most one
+// workgroup per CU); 2: 256x128 tile, one buffer, fragments in registers, two workgroups per CU; 3: 256x256 tile on
+// eight wavefronts, two buffers, one workgroup per CU (the dA W form only: the softmax layer's input gradient).
+template <typename TO, bool AT, bool BT, bool RS>
+hipError_t launch_direct_rs(const Params& P, int variant, dim3 grid, hipStream_t stream) {
+    if (variant == 2) return launch_kernel<bf16_t, TO, AT, BT, 4, 2, 2, true, RS, 2, 1>(P, grid, stream);
+    if constexpr (!AT && BT && !RS) {
+        if (variant == 3) return launch_kernel<bf16_t, TO, AT, BT, 4, 2, 4, true, false, 2, 2>(P, grid, stream);
+    }
+    if (variant == 3) return hipErrorInvalidValue;
+    if constexpr (AT && BT) {
+        if (variant == 1) return launch_kernel<bf16_t, TO, AT, BT, 2, 2, 2, true, RS, 2, 3>(P, grid, stream);
+    }
+    return launch_kernel<bf16_t, TO, AT, BT, 2, 2, 2, true, RS, 2, 2>(P, grid, stream);
+}
+template <typename TO>
+hipError_t launch_direct(const GemmDesc& d, const Params& P, int variant, dim3 grid, hipStream_t stream) {
+    if (d.atrans && d.btrans) {
+        if constexpr (sizeof(TO) == 4) {                      // (row sums go with the float weight gradients)
+            if (P.rowsum) return launch_direct_rs<TO, true, true, true>(P, variant, grid, stream);
+        }
+        if (P.rowsum) return hipErrorInvalidValue;
+        return launch_direct_rs<TO, true, true, false>(P, variant, grid, stream);
+    }
+    if (P.rowsum) return hipErrorInvalidValue;
+    if (!d.atrans && d.btrans) return launch_direct_rs<TO, false, true, false>(P, variant, grid, stream);
+    if (!d.atrans && !d.btrans) return launch_direct_rs<TO, false, false, false>(P, variant, grid, stream);
+    return hipErrorInvalidValue;
+}
+
 // The unguarded kernel applies when every tile is full, every segment's K is a whole number of
 // slabs, all loads may be of the widest kind, the per-thread offsets fit 32 bits, and the two
 // segments (if any) share their leading dimensions.
 template <typename TI>
-bool can_run_fast(const GemmDesc& d, const Params& P, int tile) {
+bool can_run_fast(const GemmDesc& d, const Params& P, int tile_m, int tile_n) {
     const int bk = CHUNKS * Vec<TI>::N;
-    if (d.M % tile || (d.Npad > 0 ? d.Npad : d.N) % tile) return false;
+    if (d.M % tile_m || (d.Npad > 0 ? d.Npad : d.N) % tile_n) return false;
     for (int s = 0; s < d.nseg; ++s) {
         if (d.seg[s].K % bk) return false;
         if (!(P.A[s].fast & 1) || !(P.B[s].fast & 1)) return false;
@@ -717,8 +916,12 @@ bool can_run_fast(const GemmDesc& d, const Params& P, int tile) {
     return true;
 }
 
-template <typename TI, typename TO>
-hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
+constexpr int kTileM[3] = {128, 256, 256}, kTileN[3] = {128, 256, 128};
+
+GemmPlan make_plan(const GemmDesc& d, bool allow_r);
+
+template <typename TI>
+Params make_params(const GemmDesc& d) {
     Params P{};
     P.nseg = d.nseg;
     for (int s = 0; s < d.nseg; ++s) {
@@ -732,26 +935,51 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
     P.add = d.add; P.ldadd = d.ldadd; P.sAdd = d.sAdd;
     P.rowsum = d.rowsum; P.sRowsum = d.sRowsum;
     P.M = d.M; P.N = d.N;
-    {
-        const size_t w = sizeof(TO) == 4 ? 16 : 8;
-        P.c_vec = aligned(d.C, w) && d.ldc % 4 == 0 && ((d.batch > 1 ? d.sC : 0) % 4 == 0);
-    }
-    const int batch = d.batch > 0 ? d.batch : 1;
-    GemmPlan plan = plan_gemm(d);
-    if (plan.big_tile && !can_run_fast<TI>(d, P, 256)) plan.big_tile = false;   // the large tile has no guarded form
-    const int tile = plan.big_tile ? 256 : 128;
-    const bool fast = can_run_fast<TI>(d, P, tile);
+    P.splits = 1;
+    return P;
+}
+// Tile counts and store modes for a tile shape; `fast`: the unguarded kernel runs.
+template <typename TO>
+void set_tiles(const GemmDesc& d, Params& P, int tm, int tn, bool fast) {
+    const size_t w = sizeof(TO) == 4 ? 16 : 8;
+    P.c_vec = aligned(d.C, w) && d.ldc % 4 == 0 && ((d.batch > 1 ? d.sC : 0) % 4 == 0);
     if (fast && d.Npad > 0) P.c_vec = 0;                 // whole tiles are computed, the stores stop at column N
     P.p_vec = (d.N % 4 == 0 && !(fast && d.Npad > 0)) ? 1 : 0;   // (the scratch itself is 256-byte aligned)
-    P.ntm = (d.M + tile - 1) / tile; P.ntn = ((fast && d.Npad > 0 ? d.Npad : d.N) + tile - 1) / tile;
+    P.ntm = (d.M + tm - 1) / tm;
+    P.ntn = ((fast && d.Npad > 0 ? d.Npad : d.N) + tn - 1) / tn;
+}
+
+template <typename TI, typename TO>
+hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
+    Params P = make_params<TI>(d);
+    const int batch = d.batch > 0 ? d.batch : 1;
+    const bool direct_form = sizeof(TI) == 2 && !d.add && !(d.atrans && !d.btrans);
+    GemmPlan plan = make_plan(d, direct_form);
+    // the plan looks at the shape only: check what it chose against the operands' alignment and fall back
+    if (plan.tile == GEMM_TILE_256X128 && !can_run_fast<TI>(d, P, 256, 128)) plan = make_plan(d, false);
+    if (plan.tile == GEMM_TILE_256 && (!can_run_fast<TI>(d, P, 256, 256) || (sizeof(TI) == 2 && !(direct_form && !d.atrans && d.btrans)))) {
+        plan = make_plan(d, false);
+        if (plan.tile == GEMM_TILE_256) { plan.tile = GEMM_TILE_128; plan.splits = 1; plan.partial_bytes = 0; plan.deep = false; }
+    }
+    const int tm = kTileM[plan.tile], tn = kTileN[plan.tile];
+    const bool fast = can_run_fast<TI>(d, P, tm, tn);
+    set_tiles<TO>(d, P, tm, tn, fast);
     P.splits = plan.splits;
     P.partial = plan.splits > 1 ? d.partial : nullptr;
     P.rs_partial = plan.splits > 1 ? d.partial + (size_t)plan.splits * batch * d.M * d.N : nullptr;
     dim3 grid((unsigned)(P.ntm * P.ntn), (unsigned)plan.splits, (unsigned)batch);
+    const bool direct = direct_form && fast;
+    const int variant = plan.tile == GEMM_TILE_256X128 ? 2 : plan.tile == GEMM_TILE_256 ? 3 : (plan.deep ? 1 : 0);
     hipError_t e;
     if (plan.splits > 1) {
         // partial tiles are float whatever the output type
-        e = plan.big_tile ? launch_form<TI, float, 4, 2, 4>(d, P, fast, false, grid, stream) : launch_form<TI, float, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
+        if constexpr (sizeof(TI) == 2) {
+            if (direct) e = launch_direct<float>(d, P, variant, grid, stream);
+            else e = launch_form<TI, float, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
+        } else {
+            e = plan.tile == GEMM_TILE_256 ? launch_form<TI, float, 4, 2, 4>(d, P, fast, false, grid, stream)
+                                           : launch_form<TI, float, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
+        }
         if (e != hipSuccess) return e;
         const long long total = (long long)d.M * d.N;
         unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
@@ -760,33 +988,48 @@ hipError_t dispatch(const GemmDesc& d, hipStream_t stream) {
                            P.rs_partial, d.rowsum, d.sRowsum, (P.c_vec && d.N % 4 == 0) ? 1 : 0);
         return hipGetLastError();
     }
-    return plan.big_tile ? launch_form<TI, TO, 4, 2, 4>(d, P, fast, false, grid, stream) : launch_form<TI, TO, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
+    if constexpr (sizeof(TI) == 2) {
+        if (direct) return launch_direct<TO>(d, P, variant, grid, stream);
+        return launch_form<TI, TO, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
+    } else {
+        return plan.tile == GEMM_TILE_256 ? launch_form<TI, TO, 4, 2, 4>(d, P, fast, false, grid, stream)
+                                          : launch_form<TI, TO, 2, 2, 2>(d, P, fast, plan.deep, grid, stream);
+    }
 }
 
-}  // namespace
-
-GemmPlan plan_gemm(const GemmDesc& d) {
-    GemmPlan p{false, false, 1, 0};
+// How a product of this shape is run.  allow_r: the 256x128 direct tile may be chosen (bf16 operands in one of its forms).
+GemmPlan make_plan(const GemmDesc& d, bool allow_r) {
+    GemmPlan p{GEMM_TILE_128, false, 1, 0};
     const int batch = d.batch > 0 ? d.batch : 1;
     const int Ne = d.Npad > 0 ? d.Npad : d.N;             // (the caller sets Npad only where the unguarded kernel applies)
     const long long t256 = (long long)((d.M + 255) / 256) * ((Ne + 255) / 256) * batch;
     const long long t128 = (long long)((d.M + 127) / 128) * ((Ne + 127) / 128) * batch;
-    // the large tile has one workgroup per CU, so its prologue and epilogue are exposed: it pays only
-    // when the contraction is long enough to amortise them
     int ktot = 0;
-    for (int s = 0; s < d.nseg; ++s) ktot += d.seg[s].K;
-    if (t256 >= 512 && !d.rowsum && ktot >= 512) { p.big_tile = true; return p; }
-    // A handful of large tiles and a very long contraction (the softmax layer's input gradient): the large
-    // tile, which moves half the operand bytes per flop, split along K over up to one workgroup per CU, if
-    // every part keeps at least 24 slabs and the parts fill three quarters of the CUs.
-    if (d.nseg == 1 && !d.add && !d.rowsum && d.partial && d.in_type == DT_BF16 && t256 <= 64 &&
-        d.M % 256 == 0 && d.N % 256 == 0 && d.seg[0].K % 64 == 0) {
-        const int slabs = d.seg[0].K / 64;
-        int s = (int)(256 / t256);
-        if (s > 16) s = 16;
-        while (s > 1 && slabs / s < 24) --s;
-        const size_t need = (size_t)s * batch * ((size_t)d.M * d.N + d.M) * sizeof(float);
-        if (s > 1 && t256 * s >= 192 && need <= d.partial_bytes) { p.big_tile = true; p.splits = s; p.partial_bytes = need; return p; }
+    bool whole_slabs = true;
+    for (int s = 0; s < d.nseg; ++s) { ktot += d.seg[s].K; whole_slabs = whole_slabs && d.seg[s].K % 64 == 0; }
+    if (d.in_type == DT_BF16) {
+        if (allow_r && d.M % 256 == 0 && Ne % 128 == 0 && whole_slabs) {
+            const long long tr = (long long)(d.M / 256) * (Ne / 128) * batch;
+            // Enough 256x128 tiles to put two on (nearly) every CU: the tile that moves 3/4 of the operand bytes of
+            // 128x128 per flop, and the only one whose loop keeps the matrix cores above half of their rate.
+            if (tr >= 480) { p.tile = GEMM_TILE_256X128; return p; }
+        }
+        // A handful of large tiles and a very long contraction (the softmax layer's input gradient, dA W form): the
+        // 256x256 tile, which moves half the operand bytes of 128x128 per flop, split along K over up to one
+        // workgroup per CU, if every part keeps at least 24 slabs and the parts fill three quarters of the CUs.
+        if (allow_r && d.nseg == 1 && !d.rowsum && d.partial && !d.atrans && d.btrans && t256 <= 64 &&
+            d.M % 256 == 0 && Ne % 256 == 0 && whole_slabs) {
+            const int slabs = d.seg[0].K / 64;
+            int s = (int)(256 / t256);
+            if (s > 16) s = 16;
+            while (s > 1 && slabs / s < 24) --s;
+            const size_t need = (size_t)s * batch * ((size_t)d.M * d.N + d.M) * sizeof(float);
+            if (s > 1 && t256 * s >= 192 && need <= d.partial_bytes) { p.tile = GEMM_TILE_256; p.splits = s; p.partial_bytes = need; return p; }
+        }
+    } else {
+        // float operands: the 256x256 tile has one workgroup per CU, so its prologue and epilogue are exposed: it pays
+        // only when the contraction is long enough to amortise them
+        if (t256 >= 512 && !d.rowsum && ktot >= 512) { p.tile = GEMM_TILE_256; return p; }
     }
     // Few output tiles and a long contraction: split K.  Up to one workgroup per CU whenever each part
     // keeps at least 8 slabs; up to two per CU (the number that fit) when each part keeps at least 64,
@@ -800,10 +1043,7 @@ GemmPlan plan_gemm(const GemmDesc& d) {
             while (s > 1 && slabs / s < min_slabs) --s;
             return s < 1 ? 1 : s;
         };
-#ifndef GEMM_SPLIT2_MIN
-#define GEMM_SPLIT2_MIN 64
-#endif
-        const int s1 = parts(256, 8), s2 = parts(512, GEMM_SPLIT2_MIN);
+        const int s1 = parts(256, 8), s2 = parts(512, 64);
         const int s = s1 > s2 ? s1 : s2;
         const size_t need = (size_t)s * batch * ((size_t)d.M * d.N + d.M) * sizeof(float);
         if (s > 1 && need <= d.partial_bytes) {
@@ -811,19 +1051,24 @@ GemmPlan plan_gemm(const GemmDesc& d) {
             p.partial_bytes = need;
         }
     }
-    // at most one 128x128 workgroup per CU: run the loads four slabs ahead instead of two
-#ifndef GEMM_DEEP_LIMIT
-#define GEMM_DEEP_LIMIT 256
-#endif
-    p.deep = t128 * p.splits <= GEMM_DEEP_LIMIT;
+    // at most one 128x128 workgroup per CU: run the loads further ahead (three LDS buffers, or four register sets)
+    p.deep = t128 * p.splits <= 256;
     return p;
+}
+
+}  // namespace
+
+GemmPlan plan_gemm(const GemmDesc& d) {
+    return make_plan(d, d.in_type == DT_BF16 && !d.add && !(d.atrans && !d.btrans));
 }
 
 size_t gemm_partial_bytes(int M, int N, int K, int batch, DType in_type) {
     GemmDesc d{};
     d.M = M; d.N = N; d.batch = batch; d.nseg = 1; d.seg[0].K = K; d.in_type = in_type;
     d.partial = reinterpret_cast<float*>(16); d.partial_bytes = ~size_t(0);
-    return plan_gemm(d).partial_bytes;
+    // the larger of what the two tile families would use: alignment decides between them only at launch time
+    const size_t a = make_plan(d, true).partial_bytes, b = make_plan(d, false).partial_bytes;
+    return a > b ? a : b;
 }
 
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t stream) {
@@ -832,6 +1077,64 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t stream) {
     if (d.in_type == DT_BF16 && d.out_type == DT_BF16) return dispatch<bf16_t, bf16_t>(d, stream);
     if (d.in_type == DT_BF16 && d.out_type == DT_F32) return dispatch<bf16_t, float>(d, stream);
     return hipErrorInvalidValue;
+}
+
+// Independent products of the dA^T X form with bf16 operands and float results, one launch for up to GROUP_MAX of
+// them (the weight gradients of several layers: together they fill the device, one by one most of them leave half of
+// it idle).
+bool gemm_group_ok(const GemmDesc* descs, int n) {
+    for (int i = 0; i < n; ++i) {
+        const GemmDesc& d = descs[i];
+        if (!(d.in_type == DT_BF16 && d.out_type == DT_F32 && d.atrans && d.btrans && !d.add && !d.bias && d.nseg == 1 && d.M > 0 && d.N > 0)) return false;
+        const Params P = make_params<bf16_t>(d);
+        if (!can_run_fast<bf16_t>(d, P, 128, 128)) return false;
+    }
+    return n > 0;
+}
+
+// Products the grouped kernel cannot take run one by one.
+hipError_t launch_gemm_group(const GemmDesc* descs, int n, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    if (n == 1) return launch_gemm(descs[0], stream);
+    if (!gemm_group_ok(descs, n)) {
+        for (int i = 0; i < n; ++i) { hipError_t e = launch_gemm(descs[i], stream); if (e != hipSuccess) return e; }
+        return hipSuccess;
+    }
+    bool all_r = true;
+    for (int i = 0; i < n && all_r; ++i) {
+        const Params P = make_params<bf16_t>(descs[i]);
+        if (!can_run_fast<bf16_t>(descs[i], P, 256, 128)) all_r = false;
+    }
+    const int tile = all_r ? GEMM_TILE_256X128 : GEMM_TILE_128;
+    for (int i0 = 0; i0 < n; i0 += GROUP_MAX) {
+        GroupParams G{};
+        G.n = n - i0 < GROUP_MAX ? n - i0 : GROUP_MAX;
+        int total = 0;
+        for (int k = 0; k < G.n; ++k) {
+            const GemmDesc& d = descs[i0 + k];
+            G.p[k] = make_params<bf16_t>(d);
+            set_tiles<float>(d, G.p[k], kTileM[tile], kTileN[tile], true);
+            G.first[k] = total;
+            total += G.p[k].ntm * G.p[k].ntn * (d.batch > 0 ? d.batch : 1);
+        }
+        G.first[G.n] = total;
+        if (all_r) {
+            constexpr size_t lds = (size_t)(256 + 128) * CHUNKS * 16;
+            static thread_local bool attr_set = false;
+            hipError_t e = allow_lds(&gemm_group_kernel<bf16_t, float, true, true, 4, 2, 2, true, true, 2, 1>, lds, &attr_set);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((gemm_group_kernel<bf16_t, float, true, true, 4, 2, 2, true, true, 2, 1>), dim3((unsigned)total), dim3(256), lds, stream, G);
+        } else {
+            constexpr size_t lds = 2 * (size_t)(128 + 128) * CHUNKS * 16;
+            static thread_local bool attr_set = false;
+            hipError_t e = allow_lds(&gemm_group_kernel<bf16_t, float, true, true, 2, 2, 2, true, true, 2, 2>, lds, &attr_set);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((gemm_group_kernel<bf16_t, float, true, true, 2, 2, 2, true, true, 2, 2>), dim3((unsigned)total), dim3(256), lds, stream, G);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace blstm

@@ -37,10 +37,13 @@ struct GemmDesc {
     DType in_type, out_type;  // in_type is the element type of A and B
 };
 
-// How a product is run: 256x256 or 128x128 tiles, and into how many K ranges it is split.
+// How a product is run: the tile shape, and into how many K ranges it is split.
+enum GemmTile { GEMM_TILE_128 = 0,        // 128x128, every element type and shape
+                GEMM_TILE_256 = 1,        // 256x256, float operands of large products
+                GEMM_TILE_256X128 = 2 };  // 256x128, bf16 operands loaded straight into LDS
 struct GemmPlan {
-    bool big_tile;
-    bool deep;                // 128x128 tile with the loads four slabs ahead (launches of at most one workgroup per CU)
+    int tile;                 // a GemmTile
+    bool deep;                // 128x128 tile with the loads further ahead (launches of at most one workgroup per CU)
     int splits;
     size_t partial_bytes;     // scratch the split needs (0 when splits == 1)
 };
@@ -50,5 +53,10 @@ size_t gemm_partial_bytes(int M, int N, int K, int batch, DType in_type);
 
 // Validates nothing (the caller's shapes are trusted); returns the launch status.
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t stream);
+// n independent products of the A^T B form (atrans and btrans, bf16 operands, float result, optional row sums, no
+// bias, one segment) in one launch where the shapes allow it (gemm_group_ok); otherwise one launch each.  A grouped
+// launch never splits along K and uses no scratch.
+bool gemm_group_ok(const GemmDesc* d, int n);
+hipError_t launch_gemm_group(const GemmDesc* d, int n, hipStream_t stream);
 
 }  // namespace blstm

@@ -16,7 +16,7 @@ from . import inputs
 class Learner:
     """Buffers of one learner: master weights, bf16 shadow, gradient, batch, workspace."""
 
-    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0, recurrent_path=0, recurrent_sync=None, overlap=None):
+    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0, recurrent_path=0, recurrent_sync=None, keep_weight_copies=True):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the HIP path has no CPU fallback")
         self.dims = dict(T=T, B=B, D=D, H=H, L=L, P=P, V=V)
@@ -25,8 +25,9 @@ class Learner:
         self.ctx = bl.blstm_create(T, B, D, H, L, P, V, mode, loss_scale)
         if recurrent_path:
             bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_RECURRENT_PATH, recurrent_path)
-        if overlap is not None:
-            bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_OVERLAP, int(overlap))
+        # the copies the passes derive from the weights are kept across steps: every method below that changes the
+        # weights reports it (weights_changed)
+        bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_KEEP_WEIGHT_COPIES, int(bool(keep_weight_copies)))
         if recurrent_sync is not None:
             bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_RECURRENT_SYNC, recurrent_sync)
         self.n = bl.blstm_param_count(self.ctx)
@@ -64,6 +65,11 @@ class Learner:
         self.theta.copy_(torch.from_numpy(theta_f32))
         if self.shadow is not None:
             bl.blstm_shadow_refresh(self.theta, self.shadow, self.n)
+        self.weights_changed()
+
+    def weights_changed(self):
+        """To be called after anything has written the weights (or the held copy) outside this class."""
+        bl.blstm_weights_changed(self.ctx)
 
     def set_batch(self, x_f32: np.ndarray, labels_i32: np.ndarray):
         self.x.copy_(torch.from_numpy(x_f32).to(self.act_dtype))
@@ -89,6 +95,7 @@ class Learner:
     def apply(self, lr, stream=None):
         """W' = apply(W, g)."""
         bl.sgd_step(self.theta, self.shadow, self.grad, self.n, lr, self.momentum, self.velocity, stream)
+        self.weights_changed()
 
     def hold(self):
         """Keeps a copy of the weights as forward/backward read them now (a device-to-device copy on
@@ -96,6 +103,7 @@ class Learner:
         if self.held is None:
             self.held = torch.empty_like(self.theta_fwd)
         self.held.copy_(self.theta_fwd)
+        self.weights_changed()
 
     def train_step(self, lr, stream=None):
         self.calgrad(stream)
@@ -131,6 +139,8 @@ def mix(learners, partner, stream=None):
     masters = [l.theta for l in learners]
     shadows = [l.shadow for l in learners] if learners[0].shadow is not None else None
     bl.adpsgd_mix(masters, shadows, learners[0].n, len(learners), partner, stream)
+    for l in learners:
+        l.weights_changed()
 
 
 # ---- the strategies of section 3.2 as orders of the library's calls, R learners in one GPU's memory ----
@@ -153,6 +163,7 @@ def adpsgd_step(learners, lr, partner, fused=False, stream=None):
             b = learners[j]
             bl.sgd_mix_pair(a.theta, b.theta, a.shadow, b.shadow, a.grad, b.grad, a.n, lr, a.momentum,
                             a.velocity, b.velocity, stream)
+            a.weights_changed(); b.weights_changed()
 
 
 def stale_adpsgd_step(learners, lr, partner, stream=None):
@@ -173,6 +184,8 @@ def sync_step(learners, lr, stream=None):
     masters = [l.theta for l in learners]
     shadows = [l.shadow for l in learners] if learners[0].shadow is not None else None
     bl.sync_average(masters, shadows, learners[0].n, len(learners), stream)
+    for l in learners:
+        l.weights_changed()
 
 
 def hybrid_step(learners, lr):
@@ -186,5 +199,6 @@ def hybrid_step(learners, lr):
     shadows = [l.shadow for l in learners] if learners[0].shadow is not None else None
     bl.sync_average(masters, shadows, learners[0].n, len(learners))
     for l in learners:
+        l.weights_changed()
         l.hold()
         l.apply(lr)
