@@ -5,15 +5,25 @@ A step is one pass of the whole hot path over one synthetic batch: blstm_forward
 softmax_xent_fwd_bwd, blstm_backward, sgd_step and one adpsgd_mix with a ring neighbour's
 replica held in the same HBM.  Inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line: frames/s of the whole job, the roofline of the kernel class that
-takes the most time (HIP events on the launch stream, recorded inside the library), and the
-float64 oracle timed on this machine's host cores on a bounded sample of the same workload.
+Prints ONE JSON line:
+  value            frames/s of the whole job (wall clock around K steps, synchronised on both sides);
+  step_ms          median and minimum of the K steps timed one by one with events on the launch stream;
+  kernel_classes   per-class durations from HIP events the library records on the launch stream;
+  roofline         the kernel that takes the largest share of the step, by kernel name, against the
+                   bf16 MFMA peak; roofline_gemm: the plain product class with the largest share;
+  adpsgd_mix ...   the streaming kernels against HBM bandwidth;
+  cpu_baseline     the float64 oracle timed on this machine's host cores on the same workload.
+HBM traffic figures ("traffic") are read from profiles/hbm_traffic_<workload>.txt, which records the
+hash of the kernel sources it was measured with; they are null when the sources have changed since.
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -25,37 +35,62 @@ PEAK_BF16_MFMA = 2.5e15      # FLOP/s, dense
 PEAK_FP32_MFMA = 157.3e12
 PEAK_HBM = 8.0e12            # B/s
 
-# HBM bytes per launch (fetch + write) of kernel classes, from rocprofv3 --pmc runs of this script
-# (FETCH_SIZE and WRITE_SIZE, each scaled by its reading for the 1 GiB copy of --traffic-calibration);
-# the runs and figures are in profiles/hbm_traffic_paper4x512.txt.  Keyed by (workload, batch, class).
-MEASURED_HBM_BYTES_PER_LAUNCH = {
-    ("paper4x512", 256, "recurrent_bwd_persistent"): (2 * 74703.8 + 129024.0) * 1024,
-    ("paper4x512", 256, "recurrent_fwd_persistent"): (2 * 64671.3 + 86016.1) * 1024,
-    ("paper4x512", 256, "gemm_logits"): (2 * 51944.5 + 336000.0) * 1024,
-    # nine launches per step: dW_x of layers 0-3 and dW_p (one kernel name, five launches), four dU_h
-    ("paper4x512", 256, "gemm_wgrad"): (2 * (5 * 75956.3 + 4 * 92284.0) + (5 * 13228.6 + 4 * 16384.0)) * 1024 / 9,
+# kernel name behind each timing class of the library (one class = one kernel function, by shape several instantiations)
+KERNEL_OF_CLASS = {
+    "recurrent_fwd_persistent": "rec_fwd_kernel", "recurrent_bwd_persistent": "rec_bwd_kernel",
+    "gemm_wgrad": "gemm_group_kernel", "softmax_rows": "softmax_rows_bf16_regs_kernel",
+    "gemm_input_projection": "gemm_kernel", "gemm_bottleneck": "gemm_kernel", "gemm_logits": "gemm_kernel",
+    "gemm_softmax_bwd": "gemm_kernel", "gemm_dgrad": "gemm_kernel", "gemm_recurrent_fwd": "gemm_kernel",
+    "gemm_recurrent_bwd": "gemm_kernel", "cell_fwd": "cell_fwd_kernel", "cell_bwd": "cell_bwd_kernel",
 }
-MEASURED_MIX_BYTES_PER_PAIR = {"paper4x512": (2 * 119318.0 + 357967.2) * 1024}   # one launch on two replicas
+
+
+def source_hash():
+    """Hash of the kernel sources: measured HBM traffic is only quoted for the sources it was measured with."""
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1904_04956_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(os.path.basename(f).encode())
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, batch):
+    """{class: HBM bytes per launch} from profiles/hbm_traffic_<workload>.txt, {} if absent or measured on other sources.
+
+    The file holds lines `sources <hash>`, `batch <B>` and `bytes_per_launch <class> <bytes>` besides its prose."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return {}
+    out, ok_src, ok_batch = {}, False, False
+    for line in open(path):
+        w = line.split()
+        if len(w) >= 2 and w[0] == "sources":
+            ok_src = w[1] == source_hash()
+        elif len(w) >= 2 and w[0] == "batch":
+            ok_batch = int(w[1]) == batch
+        elif len(w) >= 3 and w[0] == "bytes_per_launch":
+            out[w[1]] = float(w[2])
+    return out if (ok_src and ok_batch) else {}
 
 
 def flops_by_class(T, B, D, H, L, P, V):
-    """Algorithmic FLOP of one step per kernel class (2 FLOP per multiply-add), and launches."""
+    """Algorithmic FLOP of one step per kernel class (2 FLOP per multiply-add)."""
     M = T * B
     Z = P if P > 0 else 2 * H
     din = [D] + [2 * H] * (L - 1)
     f = {}
-    f["gemm_input_projection"] = (sum(2 * M * 8 * H * d for d in din), L)
-    f["gemm_recurrent_fwd"] = (L * (T - 1) * 2 * (2 * B * 4 * H * H), L * (T - 1))
-    f["gemm_bottleneck"] = (2 * M * 2 * H * P, 1 if P > 0 else 0)
-    f["gemm_logits"] = (2 * M * V * Z, 1)
-    f["gemm_softmax_bwd"] = (2 * 2 * M * V * Z, 2)
-    f["gemm_recurrent_bwd"] = (L * (T - 1) * 2 * (2 * B * 4 * H * H), L * (T - 1))
+    f["gemm_input_projection"] = sum(2 * M * 8 * H * d for d in din)
+    f["gemm_recurrent_fwd"] = L * (T - 1) * 2 * (2 * B * 4 * H * H)
+    f["gemm_bottleneck"] = 2 * M * 2 * H * P
+    f["gemm_logits"] = 2 * M * V * Z
+    f["gemm_softmax_bwd"] = 2 * 2 * M * V * Z
+    f["gemm_recurrent_bwd"] = L * (T - 1) * 2 * (2 * B * 4 * H * H)
     # the persistent kernels do a whole layer (both directions, all frames) per launch
-    f["recurrent_fwd_persistent"] = (f["gemm_recurrent_fwd"][0], L)
-    f["recurrent_bwd_persistent"] = (f["gemm_recurrent_bwd"][0], L)
-    f["gemm_wgrad"] = (sum(2 * M * 8 * H * d for d in din) + L * 2 * (T - 1) * B * 8 * H * H + 2 * M * P * 2 * H,
-                       2 * L + (1 if P > 0 else 0))
-    f["gemm_dgrad"] = (sum(2 * M * 8 * H * d for d in din[1:]) + 2 * M * 2 * H * P, L - 1 + (1 if P > 0 else 0))
+    f["recurrent_fwd_persistent"] = f["gemm_recurrent_fwd"]
+    f["recurrent_bwd_persistent"] = f["gemm_recurrent_bwd"]
+    f["gemm_wgrad"] = sum(2 * M * 8 * H * d for d in din) + L * 2 * (T - 1) * B * 8 * H * H + 2 * M * P * 2 * H
+    f["gemm_dgrad"] = sum(2 * M * 8 * H * d for d in din[1:]) + 2 * M * 2 * H * P
     return f
 
 
@@ -89,7 +124,7 @@ def main():
     import torch
     from paper_1904_04956_amd import binding as bl
     from paper_1904_04956_amd import inputs
-    from paper_1904_04956_amd.harness import Learner, mix
+    from paper_1904_04956_amd.harness import Learner
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
@@ -129,35 +164,40 @@ def main():
 
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
+    lrn.check_status()                       # synchronises; raises if a persistent kernel gave up a wait
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    lrn.check_status()
     ms_per_step = 1e3 * dt / args.steps
     frames_per_s = T * B * args.steps / dt
-    lrn.check_status()
     loss = lrn.loss_value()
+    # the same steps one by one, each bracketed by events on the launch stream
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in evs:
+        a.record(); step(); b.record()
+    torch.cuda.synchronize()
+    each = [a.elapsed_time(b) for a, b in evs]
     fpf = flop_per_frame(d["D"], d["H"], d["L"], d["P"], d["V"])
     peak = PEAK_BF16_MFMA if bf else PEAK_FP32_MFMA
 
     out = {
-        "metric": "training frames/sec (fwd+bwd+update) on 1 MI355X",
-        "value": frames_per_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if bf else "f32", "data": "synthetic",
+        "metric": "training frames/sec (fwd+bwd+update) on 1 MI355X", "value": frames_per_s, "unit": "frames/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if bf else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {d['L']}x{d['H']} BLSTM, D={d['D']}, T={T}, B={B}, P={d['P']}, V={d['V']}, "
                                f"step = forward + softmax-xent + backward + sgd_step + adpsgd_mix with one neighbour replica",
                    "global_batch": B, "seq_len": T, "lr": w.lr},
+        "step_ms": {"median": statistics.median(each), "min": min(each), "timed": "each step between two events on the launch stream"},
         "flop_per_frame": fpf,
         "pct_of_mfma_peak": 100.0 * frames_per_s * fpf / peak,
         "final_loss": loss,
     }
 
     # ---- per-kernel-class durations: HIP events recorded by the library on the launch stream ----
-    # (everything on one stream for this pass: events around a launch that shares the device with the
-    #  second stream's products would time the sharing, not the kernel)
+    traffic = measured_traffic(w.name, B)
     if not args.no_profile:
         bl.blstm_profile_enable(lrn.ctx, 1)
         nprof = min(args.steps, 10)
@@ -172,26 +212,28 @@ def main():
             if cnt == 0:
                 continue
             ent = {"ms_per_step": ms / nprof, "launches_per_step": cnt / nprof, "avg_launch_us": 1e3 * ms / cnt}
-            if name in fl and fl[name][0] > 0:
-                ent["tflops"] = fl[name][0] / (ms / nprof * 1e-3) / 1e12
+            if fl.get(name, 0) > 0:
+                ent["tflops"] = fl[name] / (ms / nprof * 1e-3) / 1e12
             classes[name] = ent
         out["kernel_classes"] = classes
-        def roofline_of(name):
-            launches = classes[name]["launches_per_step"]
-            flop_launch = fl[name][0] / launches
-            achieved = flop_launch / (classes[name]["avg_launch_us"] * 1e-6) / 1e12
-            key = (w.name, B, name)
-            return {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": peak / 1e12, "unit": "TFLOP/s",
-                    "frac": achieved * 1e12 / peak, "traffic": MEASURED_HBM_BYTES_PER_LAUNCH.get(key),
-                    "flop_per_launch": flop_launch, "avg_launch_us": classes[name]["avg_launch_us"]}
 
-        with_flop = {k: v for k, v in classes.items() if k in fl and fl[k][0] > 0}
-        if with_flop:
-            # the class that takes the most time, and the plain product class that takes the most time
-            out["roofline"] = roofline_of(max(with_flop, key=lambda k: with_flop[k]["ms_per_step"]))
-            gemm = {k: v for k, v in with_flop.items() if k.startswith("gemm_")}
-            if gemm:
-                out["roofline_gemm"] = roofline_of(max(gemm, key=lambda k: gemm[k]["ms_per_step"]))
+        def roofline_of(name):
+            c = classes[name]
+            flop_launch = fl[name] / c["launches_per_step"]
+            achieved = flop_launch / (c["avg_launch_us"] * 1e-6) / 1e12
+            return {"kernel": KERNEL_OF_CLASS.get(name, name), "class": name, "bound": "mfma", "achieved": achieved, "peak": peak / 1e12,
+                    "unit": "TFLOP/s", "frac": achieved * 1e12 / peak, "traffic": traffic.get(name),
+                    "flop_per_launch": flop_launch, "avg_launch_us": c["avg_launch_us"], "share_of_step": c["ms_per_step"] / ms_per_step}
+
+        with_flop = {k: v for k, v in classes.items() if fl.get(k, 0) > 0}
+        # time per kernel NAME: the product classes share one kernel function only nominally (different instantiations),
+        # so the dominant kernel is looked for among the classes that are one kernel each
+        single = {k: v for k, v in with_flop.items() if KERNEL_OF_CLASS.get(k) != "gemm_kernel"}
+        if single:
+            out["roofline"] = roofline_of(max(single, key=lambda k: single[k]["ms_per_step"]))
+        gemm = {k: v for k, v in with_flop.items() if k.startswith("gemm_")}
+        if gemm:
+            out["roofline_gemm"] = roofline_of(max(gemm, key=lambda k: gemm[k]["ms_per_step"]))
 
     # ---- the averaging kernel on R replicas of this model, against HBM bandwidth ----------------
     R = args.mix_replicas
@@ -212,11 +254,10 @@ def main():
         mix_ms = ev[0].elapsed_time(ev[1]) / nmix
         bytes_per = R * lrn.n * (8 + (2 if bf else 0))
         gbs = bytes_per / (mix_ms * 1e-3) / 1e9
-        out["adpsgd_mix"] = {"replicas": R, "params": lrn.n, "ms": mix_ms, "bound": "hbm", "achieved": gbs,
-                             "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": gbs * 1e9 / PEAK_HBM,
-                             "bytes_per_launch": bytes_per,
-                             "traffic": (MEASURED_MIX_BYTES_PER_PAIR[w.name] * R / 2
-                                         if w.name in MEASURED_MIX_BYTES_PER_PAIR and B == w.dims()["B"] else None)}
+        pair_traffic = traffic.get("adpsgd_mix_pair")
+        out["adpsgd_mix"] = {"kernel": "mix_kernel", "replicas": R, "params": lrn.n, "ms": mix_ms, "bound": "hbm", "achieved": gbs,
+                             "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": gbs * 1e9 / PEAK_HBM, "bytes_per_launch": bytes_per,
+                             "traffic": pair_traffic * R / 2 if pair_traffic else None}
         # the same replicas through the R-way average of the synchronous strategy (Fig. 3a)
         for it in range(2):
             bl.sync_average(reps, shs, lrn.n, R)
@@ -245,32 +286,53 @@ def main():
     out["sgd_mix_pair"] = {"ms": pair_ms, "bound": "hbm", "achieved": pair_bytes / (pair_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9,
                            "unit": "GB/s", "frac": pair_bytes / (pair_ms * 1e-3) / PEAK_HBM, "bytes_per_launch": pair_bytes,
                            "note": "one pass for both replicas' sgd_step and their adpsgd_mix (lr = 0 here so the weights stay put)"}
+    lrn.close()
 
-    # ---- the oracle on this machine's host cores, on a bounded sample of the same workload ------
+    # ---- the oracle on this machine's host cores: the same workload, whole batch, best of three steps ------------
     if not args.no_cpu_baseline:
         from oracle import blstm_oracle as orc
-        Bs = min(B, 64)
-        dd = dict(d); dd["B"] = Bs
-        dm = orc.Dims(**dd)
-        th64 = theta.astype(np.float64)
-        nb64 = th64.copy()
-        nsteps, cdt = 0, 0.0
-        t0 = time.perf_counter()
-        while nsteps < 2 or (cdt < 12.0 and nsteps < 50):     # about 12 s of oracle steps on the sample
-            _, g = orc.loss_and_grad(dm, th64, x[:, :Bs], labels[:, :Bs])
-            th64, _ = orc.sgd_step(th64, g, w.lr)
-            th64, nb64 = orc.adpsgd_mix([th64, nb64], [1, 0])
-            nsteps += 1
-            cdt = time.perf_counter() - t0
         try:
-            from threadpoolctl import threadpool_info
+            from threadpoolctl import threadpool_info, threadpool_limits
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
+            threadpool_limits = None
             cores = os.cpu_count()
-        out["cpu_baseline"] = {"value": T * Bs * nsteps / cdt, "unit": "frames/s", "cores": cores, "kind": "oracle",
-                               "sample": f"{nsteps} steps (loss, gradient, SGD update, pair averaging) of the same model on the "
-                                         f"first {Bs} of {B} sequences, float64 numpy, {cdt:.1f} s"}
-    lrn.close()
+
+        def oracle_step(dm, th64, nb64, xx, ll, lr):
+            _, g = orc.loss_and_grad(dm, th64, xx, ll)
+            th64, _ = orc.sgd_step(th64, g, lr)
+            return orc.adpsgd_mix([th64, nb64], [1, 0])
+
+        dm = orc.Dims(**d)
+        th64 = theta.astype(np.float64)
+        nb64 = th64.copy()
+        times = []
+        budget0 = time.perf_counter()
+        for _ in range(3):
+            t0 = time.perf_counter()
+            th64, nb64 = oracle_step(dm, th64, nb64, x, labels, w.lr)
+            times.append(time.perf_counter() - t0)
+            if time.perf_counter() - budget0 > 25.0:      # bounded: about half a minute at most
+                break
+        best = min(times)
+        out["cpu_baseline"] = {"value": T * B / best, "unit": "frames/s", "cores": cores, "kind": "oracle",
+                               "sample": f"best of {len(times)} whole steps (loss, gradient, SGD update, pair averaging) of the same "
+                                         f"workload, all {B} sequences, float64 numpy, {best:.2f} s per step"}
+        # one thread, the tiny workload (the case the oracle finishes in milliseconds)
+        if threadpool_limits is not None:
+            tw = inputs.WORKLOADS["tiny"]
+            tdm = orc.Dims(**tw.dims())
+            tth = inputs.make_theta(orc.param_count(tdm), tw.seed).astype(np.float64)
+            tx, tl = inputs.make_batch(tw.T, tw.B, tw.D, tw.V, tw.seed)
+            with threadpool_limits(limits=1):
+                tt = []
+                tnb = tth.copy()
+                for _ in range(5):
+                    t0 = time.perf_counter()
+                    tth, tnb = oracle_step(tdm, tth, tnb, tx, tl, tw.lr)
+                    tt.append(time.perf_counter() - t0)
+            out["cpu_baseline"]["tiny_workload_one_thread"] = {"value": tw.T * tw.B / min(tt), "unit": "frames/s", "cores": 1,
+                                                               "sample": f"best of 5 whole steps of the tiny workload, {min(tt) * 1e3:.1f} ms per step"}
     print(json.dumps(out))
 
 

@@ -7,13 +7,6 @@
 namespace blstm {
 namespace {
 
-// tuning constants (overridable at build time for sweeps)
-#ifndef BLSTM_MIX_UNROLL
-#define BLSTM_MIX_UNROLL 4
-#endif
-#ifndef BLSTM_MIX_BLOCKS
-#define BLSTM_MIX_BLOCKS (256 * 16)
-#endif
 constexpr int UPD_THREADS = 256;
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
@@ -48,39 +41,42 @@ __global__ __launch_bounds__(UPD_THREADS) void sgd_kernel(float* __restrict__ th
     }
 }
 
-// Both members of pair blockIdx.y become their average.  Four independent 16-byte loads per operand
-// are issued before the first store so that enough bytes are in flight to cover HBM latency.
+// Both members of pair blockIdx.y become their average.  A workgroup owns one contiguous span of MIX_SPAN 16-byte
+// words of the pair (many small workgroups, each streaming one 16 KB piece per operand, measured a few percent above
+// a grid-stride walk); its four independent 16-byte loads per operand are issued before the first store so that
+// enough bytes are in flight to cover HBM latency.  Non-temporal loads and stores.
+constexpr int MIX_U = 4;
+constexpr size_t MIX_SPAN = (size_t)MIX_U * UPD_THREADS;
 template <bool SHADOW>
 __global__ __launch_bounds__(UPD_THREADS) void mix_kernel(MixPairs p, size_t n) {
-    constexpr int U = BLSTM_MIX_UNROLL;
     const int pr = blockIdx.y;
     f32x4_t* __restrict__ a = reinterpret_cast<f32x4_t*>(p.a[pr]);
     f32x4_t* __restrict__ b = reinterpret_cast<f32x4_t*>(p.b[pr]);
     u32x2_t* __restrict__ sa = reinterpret_cast<u32x2_t*>(p.sa[pr]);
     u32x2_t* __restrict__ sb = reinterpret_cast<u32x2_t*>(p.sb[pr]);
     const size_t n4 = n / 4;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + (U - 1) * stride < n4; i += U * stride) {
-        f32x4_t x[U], y[U];
+    const size_t i = (size_t)blockIdx.x * MIX_SPAN + threadIdx.x;
+    if ((size_t)(blockIdx.x + 1) * MIX_SPAN <= n4) {        // a whole span
+        f32x4_t x[MIX_U], y[MIX_U];
 #pragma unroll
-        for (int k = 0; k < U; ++k) { x[k] = __builtin_nontemporal_load(a + i + k * stride); y[k] = __builtin_nontemporal_load(b + i + k * stride); }
+        for (int k = 0; k < MIX_U; ++k) { x[k] = __builtin_nontemporal_load(a + i + k * UPD_THREADS); y[k] = __builtin_nontemporal_load(b + i + k * UPD_THREADS); }
 #pragma unroll
-        for (int k = 0; k < U; ++k) {
+        for (int k = 0; k < MIX_U; ++k) {
             const f32x4_t m = 0.5f * (x[k] + y[k]);
-            __builtin_nontemporal_store(m, a + i + k * stride);
-            __builtin_nontemporal_store(m, b + i + k * stride);
+            __builtin_nontemporal_store(m, a + i + k * UPD_THREADS);
+            __builtin_nontemporal_store(m, b + i + k * UPD_THREADS);
             if (SHADOW) {
                 u32x2_t s; s[0] = pack_bf2(m[0], m[1]); s[1] = pack_bf2(m[2], m[3]);
-                __builtin_nontemporal_store(s, sa + i + k * stride);
-                __builtin_nontemporal_store(s, sb + i + k * stride);
+                __builtin_nontemporal_store(s, sa + i + k * UPD_THREADS);
+                __builtin_nontemporal_store(s, sb + i + k * UPD_THREADS);
             }
         }
-    }
-    for (; i < n4; i += stride) {
-        const f32x4_t m = 0.5f * (a[i] + b[i]);
-        a[i] = m; b[i] = m;
-        if (SHADOW) { u32x2_t s; s[0] = pack_bf2(m[0], m[1]); s[1] = pack_bf2(m[2], m[3]); sa[i] = s; sb[i] = s; }
+    } else {                                               // the last, partial span
+        for (size_t j = i; j < n4; j += UPD_THREADS) {
+            const f32x4_t m = 0.5f * (a[j] + b[j]);
+            a[j] = m; b[j] = m;
+            if (SHADOW) { u32x2_t s; s[0] = pack_bf2(m[0], m[1]); s[1] = pack_bf2(m[2], m[3]); sa[j] = s; sb[j] = s; }
+        }
     }
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
         const size_t j = n4 * 4 + threadIdx.x;
@@ -202,8 +198,8 @@ hipError_t launch_sgd(float* theta, unsigned short* shadow, const float* grad, s
 
 hipError_t launch_mix(const MixPairs& p, size_t n, hipStream_t st) {
     if (n == 0 || p.npairs == 0) return hipSuccess;
-    unsigned per_pair = blocks_for(n / 4, (BLSTM_MIX_BLOCKS + p.npairs - 1) / p.npairs);
-    dim3 grid(per_pair, (unsigned)p.npairs), block(UPD_THREADS);
+    const size_t spans = (n / 4 + MIX_SPAN - 1) / MIX_SPAN;
+    dim3 grid((unsigned)(spans < 1 ? 1 : spans), (unsigned)p.npairs), block(UPD_THREADS);
     if (p.sa[0]) hipLaunchKernelGGL(mix_kernel<true>, grid, block, 0, st, p, n);
     else hipLaunchKernelGGL(mix_kernel<false>, grid, block, 0, st, p, n);
     return hipGetLastError();
