@@ -631,9 +631,10 @@ __device__ __forceinline__ void gemm_tile(const Params& P, int lin, const int sp
 
     // Epilogue: accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32.
     if constexpr (FAST) {
-        // Full tiles go through LDS (free after the loop's last barrier), 128 tile rows at a time, so that every
-        // store instruction writes whole rows: 16 bytes (float) or 8 bytes (bf16) per lane.  A wavefront's 4-byte
-        // store costs the memory pipeline as much as a 16-byte one, and a tile has a quarter as many of the latter.
+        // Full tiles go through LDS (free after the loop's last barrier), 64 or 128 tile rows at a time, so that every
+        // store instruction writes whole rows, 16 bytes per lane (four floats or eight bf16).  A wavefront's store
+        // costs the memory pipeline about the same whatever its width, so the number of store instructions is what
+        // an output-heavy product (the logits: K = 256) pays for.
         // The same for the float partial tiles of a split.  16-byte column groups are XOR-swizzled with the row so
         // that both sides spread over the banks.
         const bool to_part = P.splits > 1;
@@ -645,41 +646,59 @@ __device__ __forceinline__ void gemm_tile(const Params& P, int lin, const int sp
             constexpr int LDSB = (NS > 0 ? NS : 2) * STAGE * 16;
             constexpr int RR = 128 * BN * 4 <= LDSB ? 128 : 64;   // tile rows per round: RR x BN floats fit the LDS of the main loop
             static_assert(RR * BN * 4 <= LDSB, "a round of the staged epilogue must fit the LDS of the main loop");
-            constexpr int GPR = BN / 4, RPP = NT / GPR;     // 16-byte groups per row, rows per pass of the stores
+            // A round stages RR tile rows: the row blocks h IBR .. h IBR + IBR - 1 of BOTH wave rows, so that every
+            // wavefront takes part in every round.  Staging row s = wm 32 IBR + ib 32 + r is tile row
+            // wm 32 TM + (h IBR + ib) 32 + r.
+            constexpr int IBR = RR / 64, ROUNDS = TM / IBR;
+            static_assert(TM % IBR == 0, "row blocks per round divide the wave tile");
+            auto tile_row = [](int s, int h) { return (s / (32 * IBR)) * (32 * TM) + h * IBR * 32 + (s % (32 * IBR)); };
+            constexpr int GPR = BN / 4, RPP = NT / GPR;     // 16-byte float groups per row, rows per pass of the stores
+            constexpr int GPR8 = BN / 8, RPP8 = NT / GPR8;  // the same for eight bf16 per lane
 #pragma unroll
-            for (int h = 0; h < BM / RR; ++h) {
+            for (int h = 0; h < ROUNDS; ++h) {
                 if (h > 0) __syncthreads();
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int col = wn * (32 * TN) + j * 32 + (lane & 31);
                     const float bv = bz ? ld_f(bz + col0 + col) : 0.0f;
 #pragma unroll
-                    for (int i = 0; i < TM; ++i) {
-                        const int tr = wm * (32 * TM) + i * 32;            // first tile row of this accumulator block
-                        if (tr / RR != h) continue;                        // (uniform per wavefront)
+                    for (int ib = 0; ib < IBR; ++ib) {
+                        const int i = h * IBR + ib;
 #pragma unroll
                         for (int e = 0; e < 16; ++e) {
-                            const int row = tr - h * RR + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                            const int row = wm * (32 * IBR) + ib * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
                             cs[row * BN + ((((col >> 2) ^ (row & 7))) << 2) + (col & 3)] = acc[i][j][e] + bv;
                         }
                     }
                 }
                 __syncthreads();
-                const int g = tid % GPR;
                 if (to_part) {
-                    float* dst0 = part + (long long)(row0 + h * RR) * P.N + col0 + 4 * g;
+                    const int g = tid % GPR;
+                    float* dst0 = part + (long long)row0 * P.N + col0 + 4 * g;
 #pragma unroll 4
                     for (int pass = 0; pass < RR / RPP; ++pass) {
                         const int r = pass * RPP + tid / GPR;
-                        *reinterpret_cast<float4*>(dst0 + (long long)r * P.N) = *reinterpret_cast<const float4*>(&cs[r * BN + ((g ^ (r & 7)) << 2)]);
+                        *reinterpret_cast<float4*>(dst0 + (long long)tile_row(r, h) * P.N) = *reinterpret_cast<const float4*>(&cs[r * BN + ((g ^ (r & 7)) << 2)]);
+                    }
+                } else if (sizeof(TO) == 2 && P.c_vec == 2) {   // eight bf16 per lane: 16-byte stores
+                    const int g = tid % GPR8;
+                    TO* dst0 = Cz + (long long)row0 * P.ldc + col0 + 8 * g;
+#pragma unroll 4
+                    for (int pass = 0; pass < RR / RPP8; ++pass) {
+                        const int r = pass * RPP8 + tid / GPR8;
+                        const float4 v = *reinterpret_cast<const float4*>(&cs[r * BN + (((2 * g) ^ (r & 7)) << 2)]);
+                        const float4 w = *reinterpret_cast<const float4*>(&cs[r * BN + (((2 * g + 1) ^ (r & 7)) << 2)]);
+                        *reinterpret_cast<uint4*>(dst0 + (long long)tile_row(r, h) * P.ldc) =
+                            make_uint4(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w), pack_bf2(w.x, w.y), pack_bf2(w.z, w.w));
                     }
                 } else {
-                    TO* dst0 = Cz + (long long)(row0 + h * RR) * P.ldc + col0 + 4 * g;
+                    const int g = tid % GPR;
+                    TO* dst0 = Cz + (long long)row0 * P.ldc + col0 + 4 * g;
 #pragma unroll 4
                     for (int pass = 0; pass < RR / RPP; ++pass) {
                         const int r = pass * RPP + tid / GPR;
                         const float4 v = *reinterpret_cast<const float4*>(&cs[r * BN + ((g ^ (r & 7)) << 2)]);
-                        TO* dst = dst0 + (long long)r * P.ldc;
+                        TO* dst = dst0 + (long long)tile_row(r, h) * P.ldc;
                         if constexpr (sizeof(TO) == 4) *reinterpret_cast<float4*>(dst) = v;
                         else *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w));
                     }
@@ -943,6 +962,7 @@ template <typename TO>
 void set_tiles(const GemmDesc& d, Params& P, int tm, int tn, bool fast) {
     const size_t w = sizeof(TO) == 4 ? 16 : 8;
     P.c_vec = aligned(d.C, w) && d.ldc % 4 == 0 && ((d.batch > 1 ? d.sC : 0) % 4 == 0);
+    if (sizeof(TO) == 2 && P.c_vec && aligned(d.C, 16) && d.ldc % 8 == 0 && ((d.batch > 1 ? d.sC : 0) % 8 == 0)) P.c_vec = 2;   // 16-byte bf16 stores
     if (fast && d.Npad > 0) P.c_vec = 0;                 // whole tiles are computed, the stores stop at column N
     P.p_vec = (d.N % 4 == 0 && !(fast && d.Npad > 0)) ? 1 : 0;   // (the scratch itself is 256-byte aligned)
     P.ntm = (d.M + tm - 1) / tm;
