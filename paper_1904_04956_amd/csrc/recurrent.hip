@@ -806,22 +806,27 @@ __global__ void fill_u32_kernel(unsigned* p, int n, unsigned v) {
     if (i < n) p[i] = v;
 }
 
+// Whether `grid` workgroups of this kernel can be resident at once (the persistent kernels wait on each other).  The
+// attribute call and the occupancy query are made once per kernel instantiation and thread; the answer depends on
+// the kernel and the device only, so it is kept (cache: per instantiation, one slot).
+struct FitCache { bool known; int per_device; };
 template <typename K>
-hipError_t prepare(K kernel, int threads, size_t dyn_lds, int grid, bool* fits) {
-    static thread_local int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
+hipError_t prepare(K kernel, int threads, size_t dyn_lds, int grid, FitCache* cache, bool* fits) {
+    if (!cache->known) {
+        int dev = 0, cus = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
         e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds);
+        if (e != hipSuccess) return e;
+        int per_cu = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, dyn_lds);
+        if (e != hipSuccess) return e;
+        cache->per_device = per_cu * cus;
+        cache->known = true;
     }
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_lds);
-    if (e != hipSuccess) return e;
-    int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, dyn_lds);
-    if (e != hipSuccess) return e;
-    *fits = (long long)per_cu * cus >= grid;
+    *fits = cache->per_device >= grid;
     return hipSuccess;
 }
 
@@ -829,7 +834,8 @@ template <int NW, int KW, bool S, bool FULL, bool MULTI>
 hipError_t run_fwd_m(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched) {
     const size_t lds = (size_t)NW * 4 * 4 * 64 * 16 + (size_t)NW * 512;   // partial sums; regrouping of h, 512 bytes per wavefront
     bool fits = false;
-    hipError_t e = prepare(rec_fwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &fits);
+    static thread_local FitCache cache{false, 0};
+    hipError_t e = prepare(rec_fwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &cache, &fits);
     if (e != hipSuccess || !fits) return e;
     hipLaunchKernelGGL((rec_fwd_kernel<NW, KW, S, FULL, MULTI>), dim3(grid), dim3(64 * NW), lds, st, a);
     *launched = true;
@@ -847,7 +853,8 @@ template <int NW, int KW, bool S, bool FULL, bool MULTI>
 hipError_t run_bwd_m(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
     const size_t lds = (size_t)NW * 4 * 64 * 16 + (size_t)NW * 2048;   // partial sums; regrouping of dE/da, 2 KB per wavefront
     bool fits = false;
-    hipError_t e = prepare(rec_bwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &fits);
+    static thread_local FitCache cache{false, 0};
+    hipError_t e = prepare(rec_bwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &cache, &fits);
     if (e != hipSuccess || !fits) return e;
     hipLaunchKernelGGL((rec_bwd_kernel<NW, KW, S, FULL, MULTI>), dim3(grid), dim3(64 * NW), lds, st, a);
     *launched = true;

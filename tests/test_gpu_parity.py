@@ -217,6 +217,13 @@ def test_persistent_and_stepwise_paths_agree():
     assert rel_err(res[0][1], res[1][1]) <= 2e-2
 
 
+def test_weight_gradients_in_more_than_one_grouped_launch():
+    # seven layers: fifteen weight-gradient products, more than one grouped launch holds; padded first layer among them
+    check_step(dict(T=4, B=32, D=130, H=128, L=7, P=128, V=256), 1, seed=84, theta_scale=2.0)
+    # shapes the 256x128 tile takes (4H = 2048, M = 256) and a layer count that fills one grouped launch exactly
+    check_step(dict(T=8, B=32, D=128, H=512, L=1, P=128, V=384), 1, seed=85, theta_scale=2.0)
+
+
 def test_kept_weight_copies_change_nothing():
     # the copies derived from the weights (padded W_x of layer 0, transposed U_h), kept across steps and refreshed on
     # blstm_weights_changed, must give the same bits as copies rebuilt in every pass
