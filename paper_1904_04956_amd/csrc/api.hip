@@ -66,6 +66,7 @@ struct blstm_ctx {
     int rec_nbg, rec_tiles;   // batch groups per direction and 32-row tiles per group of the persistent kernels
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
+    bool dax_filled;          // the forward pass's persistent kernels have marked every exchange copy of dE/da "not written yet"
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
     bool test_abort;          // failure-handling tests: the next forward pass raises the abort word itself
     bool keep_copies;         // the caller reports weight changes (blstm_weights_changed): derived copies are kept across steps
@@ -272,6 +273,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     }
     // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
     c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false; c->test_abort = false;
+    c->dax_filled = false;
     c->fwd_persistent.assign(c->L, 0);
     c->wUHT = w; c->wCNT = w; c->wHX = w; c->wDAX = w; c->hx_bytes = 0; c->dax_bytes = 0;
     if (c->st == DT_BF16 && rec_waves_for(c->H, c->B) > 0) {
@@ -365,6 +367,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
     float* AX = reinterpret_cast<float*>(ctx->ws + ctx->wAX);
     float* PRE = reinterpret_cast<float*>(ctx->ws + ctx->wPRE);
     ctx->have_forward = false;
+    ctx->dax_filled = false;
     const bool persistent = ctx->rec_nbg > 0 && ctx->rec_path == 0;
     if (persistent && ctx->rec_sync == 1)    // h of every layer starts as "not written yet"
         RUN(PC_MISC, "sentinel fill of h", launch_fill_bytes16(ctx->ws + ctx->wHX, ctx->hx_bytes * ctx->L, 0xFFFFFFFFu, st));
@@ -418,6 +421,10 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
             a.gates = reinterpret_cast<unsigned short*>(G); a.c = C;
             a.cnt = cnt; a.abort_word = cnt + ncnt; a.limit_ticks = 200000000ull;
             a.T = T; a.B = B; a.H = H; a.nbg = ctx->rec_nbg; a.tiles_per_group = ctx->rec_tiles;
+            if (ctx->rec_sync == 1 && rec_fwd_fills(H)) {   // the backward twin's exchange copy is pre-filled on the side
+                a.fill = ctx->ws + ctx->wDAX + ctx->dax_bytes * l;
+                a.fill_words = ctx->dax_bytes / 16;
+            }
             bool launched = false;
             RUN(PC_REC_FWD, "persistent recurrent forward", launch_rec_fwd(a, ctx->rec_sync == 1, st, &launched));
             ctx->fwd_persistent[l] = launched ? 1 : 0;
@@ -464,6 +471,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
         RUN(PC_MISC, "copy of the LSTM output", hipMemcpyAsync(z_out, YL, (size_t)M * 2 * H * e, hipMemcpyDeviceToDevice, st));
     }
     ctx->have_forward = true;
+    ctx->dax_filled = persistent && ctx->rec_sync == 1 && rec_fwd_fills(H);
     return BLSTM_OK;
 }
 
@@ -532,9 +540,12 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
         RUN(PC_MISC, "U_h transposes", launch_transpose_uh(ta, H, st));
         ctx->uht_of = theta;
     }
-    // In sentinel mode every layer's exchange copy of dE/da starts as "not written yet": one fill.
-    if (sentinel)
+    // In sentinel mode every layer's exchange copy of dE/da starts as "not written yet": the forward pass's persistent
+    // kernels have seen to that, each for its layer; otherwise (protocol switched in between, a second backward pass on
+    // one forward pass) one fill.
+    if (sentinel && !ctx->dax_filled)
         RUN(PC_MISC, "sentinel fill of da", launch_fill_bytes16(ctx->ws + ctx->wDAX, ctx->dax_bytes * ctx->L, 0xFFFFFFFFu, st));
+    ctx->dax_filled = false;
     const char* dY;
     int next_buf = 0;
     if (P > 0) {

@@ -47,6 +47,10 @@ struct RecFwdArgs {
     unsigned* cnt;                // [2*nbg][tiles_per_group] counters, zero before the launch
     unsigned* abort_word;         // raised when a wait ran out of time
     unsigned long long limit_ticks;   // wait limit in ticks of the 100 MHz wall clock
+    // fill_words 16-byte words at `fill` are set to 0xFF bytes while the kernel runs (the backward kernel's exchange copy
+    // of this layer, marked "not written yet" off the frame-to-frame path instead of by a launch of its own); null: none
+    void* fill;
+    unsigned long long fill_words;
     int T, B, H, nbg, tiles_per_group;
 };
 struct RecBwdArgs {
@@ -64,6 +68,8 @@ struct RecBwdArgs {
 };
 // Wavefronts per workgroup of the persistent kernels for this H, 0 if H is not supported.
 int rec_waves_for(int H, int B);
+// Whether launch_rec_fwd for this width honours RecFwdArgs::fill.
+bool rec_fwd_fills(int H);
 // *launched is false (and nothing was enqueued) when the grid cannot be co-resident on this device.
 hipError_t launch_rec_fwd(const RecFwdArgs& a, bool sentinel, hipStream_t st, bool* launched);
 hipError_t launch_rec_bwd(const RecBwdArgs& a, bool sentinel, hipStream_t st, bool* launched);

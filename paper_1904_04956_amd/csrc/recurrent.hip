@@ -226,7 +226,23 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
     const int ntl = tiles_in_batch(gm.bg, a.tiles_per_group, B);
-    if (ntl == 0) return;
+    // This workgroup's share of the region to fill (the widest slice of U_h leaves no register for it: KW <= 128 only):
+    // words [fill_pos, fill_end) of its share, a few words per thread and item.
+    constexpr bool FILLS = KW <= 128;
+    const unsigned long long fill_per_wg = (FILLS && a.fill) ? (a.fill_words + gridDim.x - 1) / gridDim.x : 0ull;
+    const unsigned long long fill_begin = min(a.fill_words, (unsigned long long)blockIdx.x * fill_per_wg);
+    uint4* const fill_base = static_cast<uint4*>(a.fill) + fill_begin;                     // uniform
+    const unsigned fill_end = (unsigned)(min(a.fill_words, fill_begin + fill_per_wg) - fill_begin);   // (a share is far below 2^32 words)
+    unsigned fill_pos = threadIdx.x;
+    const int fill_per_item = ntl > 0 ? (int)((fill_per_wg + (unsigned long long)(64 * NW) * (T * ntl) - 1) / ((unsigned long long)(64 * NW) * (T * ntl))) : 0;
+    auto fill_some = [&](int words) __attribute__((always_inline)) {
+        if constexpr (FILLS)
+            for (int k = 0; k < words && fill_pos < fill_end; ++k, fill_pos += 64 * NW) fill_base[fill_pos] = make_uint4(~0u, ~0u, ~0u, ~0u);
+    };
+    if (ntl == 0) {                                      // no batch tile of its own: only its share of the fill
+        if constexpr (FILLS) while (fill_pos < fill_end) fill_some(1 << 20);
+        return;
+    }
 
     // this wavefront's slice of U_h as B-fragments: unit row l32 of each gate, 8 consecutive k per lane
     uint4 bfrag[4][KSTEPS];
@@ -314,6 +330,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         const int xrow_ = 2 * EPT * (int)(threadIdx.x >> 6) + 4 * (lane_ >> 5) + ((lane_ >> 3) & 3);
         const unsigned xcol_ = (unsigned)(u * 32 + 8 * ((lane_ >> 1) & 3) + 4 * (lane_ & 1));
         if (tail.xok) *reinterpret_cast<uint2*>(yb + ((unsigned)xrow_ * (unsigned)(2 * H) + (unsigned)(d * H) + xcol_)) = tail.hq;
+        fill_some(fill_per_item);
     };
     auto do_item = [&](const int item, const float (&ax)[EPT][4], const float (&cpl)[EPT], float (&axn)[EPT][4],
                        float (&cpn)[EPT]) __attribute__((always_inline)) {
@@ -492,6 +509,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         }
     }
     flush_tail();
+    if constexpr (FILLS) while (fill_pos < fill_end) fill_some(1 << 20);   // (whatever rounding left over)
 }
 
 // ------------------------------------------------------------------------------ backward
@@ -875,6 +893,9 @@ hipError_t run_bwd(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched
 // (32, 64, 128, 256 elements each: four batch rows per thread in every variant).  At H = 1024 the U_h
 // slice fills 256 registers per lane, which leaves no room for the predicates of a ragged batch, so
 // that width needs B to be a multiple of 32.  Returns the wavefronts per workgroup, 0 if unsupported.
+// Whether the forward kernel for this width also fills RecFwdArgs::fill (the widest one has no register to spare).
+bool rec_fwd_fills(int H) { return H == 128 || H == 256 || H == 512; }
+
 int rec_waves_for(int H, int B) {
     if (H == 128 || H == 256 || H == 512) return 4;
     if (H == 1024 && B % 32 == 0) return 4;
