@@ -85,7 +85,8 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
 /* Softmax cross-entropy over V classes (Eq. 1a with the frame-level criterion) and its gradients:
    loss_dev[0] = s * sum -log p[label]; dz = dE/dz [T][B][P or 2H];
    grad: only the W_s and b_s slices are written (overwritten, not accumulated).
-   labels [T][B] int32 in [0, V); out-of-range labels are not detected. */
+   labels [T][B] int32 in [0, V).  A label outside that range is never used as an index: its frame's loss term, and
+   with it the loss, becomes NaN. */
 int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const int32_t* labels,
                          float* loss_dev, void* dz, float* grad, void* stream);
 

@@ -116,15 +116,6 @@ int check_hip(hipError_t e, const char* what) {
         if (e_ != hipSuccess) return check_hip(e_, what);            \
     } while (0)
 
-#define RUN_ON(strm, cls, what, expr)                                \
-    do {                                                             \
-        hipError_t e_;                                               \
-        { Scope sc_(ctx, strm, cls); e_ = (expr); }                  \
-        if (e_ != hipSuccess) return check_hip(e_, what);            \
-    } while (0)
-#define HIPCHK(what, expr)                                           \
-    do { hipError_t e_ = (expr); if (e_ != hipSuccess) return check_hip(e_, what); } while (0)
-
 GemmDesc gemm_desc(const blstm_ctx* c, DType in, DType out) {
     GemmDesc d{};
     d.nseg = 1; d.batch = 1; d.in_type = in; d.out_type = out;

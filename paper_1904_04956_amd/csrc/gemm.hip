@@ -274,9 +274,10 @@ __device__ __forceinline__ void mma(f32x16_t& acc, const uint4& a, const uint4& 
 // one barrier per slab.  NS = 1: one LDS buffer; all fragments of a slab are read into registers, a barrier frees the
 // buffer for the next slab's loads, and the products run from registers while those loads are in flight; workgroups
 // sharing a CU take turns on the matrix cores (one multiplies while another reads its fragments).
-// `lin`, `split`, `z`: tile index within the product, K range and batch index of this workgroup.
+// `lin`, `split`, `z`: tile index within the product, K range and batch index of this workgroup; xcd_remap: lin is
+// the workgroup id of a launch of this product alone and is still to be regrouped by XCD (below).
 template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D, int NS>
-__device__ __forceinline__ void gemm_tile(const Params& P, int lin, const int split, const int z) {
+__device__ __forceinline__ void gemm_tile(const Params& P, int lin, const int split, const int z, const bool xcd_remap) {
     static_assert(NS == 0 || (FAST && sizeof(TI) == 2 && D == 2), "direct mode is built for the unguarded 16-bit form");
     static_assert(D == 2 || (D == 4 && FAST && WN == 2), "the deep pipeline exists for the unguarded 128x128 tile only");
     static_assert(WN == 2 || (FAST && !RS), "the eight-wave shape exists in the unguarded form only");
@@ -298,7 +299,7 @@ __device__ __forceinline__ void gemm_tile(const Params& P, int lin, const int sp
     // range of tiles so that its L2 sees neighbouring tiles, then walk the range in bands
     // of eight tile rows so that concurrently resident tiles share A rows and B columns.
     const int nt = P.ntm * P.ntn;
-    {
+    if (xcd_remap) {
         const int nt8 = nt & ~7;
         if (lin < nt8) lin = (lin & 7) * (nt8 >> 3) + (lin >> 3);
     }
@@ -755,11 +756,15 @@ constexpr int occupancy_target() {
 
 template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D, int NS>
 __global__ __launch_bounds__(128 * WN, (occupancy_target<TM, TN, WN, D, NS>())) void gemm_kernel(Params P) {
-    gemm_tile<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D, NS>(P, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
+    gemm_tile<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D, NS>(P, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, true);
 }
 
-// Several independent products of one form in one launch (the weight gradients of all layers): workgroup x belongs
-// to the product g with first[g] <= x < first[g + 1]; within it, tiles are numbered batch-major.  No split along K.
+// Several independent products of one form in one launch (the weight gradients of all layers).  All tiles of all
+// products are numbered in one sequence (product by product, batch-major within a product); workgroup ids are dealt
+// round-robin to the eight XCDs, so XCD x takes the x-th eighth of that sequence: the tiles that run at the same time
+// on one XCD then belong to one or two products and share their operand panels in that XCD's L2 (with every XCD
+// walking every product, each L2 fetched its own copy of every panel: 3.4 times the algorithmic bytes, and the launch
+// ran at the HBM-side bandwidth).  Tile v belongs to the product g with first[g] <= v < first[g + 1].  No split along K.
 constexpr int GROUP_MAX = 12;
 struct GroupParams {
     Params p[GROUP_MAX];
@@ -768,12 +773,14 @@ struct GroupParams {
 };
 template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D, int NS>
 __global__ __launch_bounds__(128 * WN, (occupancy_target<TM, TN, WN, D, NS>())) void gemm_group_kernel(GroupParams G) {
-    const int x = (int)blockIdx.x;
+    int x = (int)blockIdx.x;
+    const int total8 = G.first[G.n] & ~7;
+    if (x < total8) x = (x & 7) * (total8 >> 3) + (x >> 3);
     int g = 0;
     for (int k = 1; k < G.n; ++k) if (x >= G.first[k]) g = k;
     const Params& P = G.p[g];
     const int local = x - G.first[g], per = P.ntm * P.ntn;
-    gemm_tile<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D, NS>(P, local % per, 0, local / per);
+    gemm_tile<TI, TO, AT, BT, TM, TN, WN, FAST, RS, D, NS>(P, local % per, 0, local / per, false);
 }
 
 // C[m][n] = sum over splits of partial[z][s][m][n] (+ bias[n]) in the order s = 0, 1, ...
@@ -1086,9 +1093,14 @@ size_t gemm_partial_bytes(int M, int N, int K, int batch, DType in_type) {
     GemmDesc d{};
     d.M = M; d.N = N; d.batch = batch; d.nseg = 1; d.seg[0].K = K; d.in_type = in_type;
     d.partial = reinterpret_cast<float*>(16); d.partial_bytes = ~size_t(0);
-    // the larger of what the two tile families would use: alignment decides between them only at launch time
-    const size_t a = make_plan(d, true).partial_bytes, b = make_plan(d, false).partial_bytes;
-    return a > b ? a : b;
+    // the largest of what the tile families would use in any operand form: alignment decides between them only at launch time
+    size_t need = make_plan(d, false).partial_bytes;
+    for (int form = 0; form < 3; ++form) {
+        d.atrans = form == 2; d.btrans = form >= 1;
+        const size_t a = make_plan(d, true).partial_bytes;
+        if (a > need) need = a;
+    }
+    return need;
 }
 
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t stream) {

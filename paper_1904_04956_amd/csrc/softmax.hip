@@ -30,13 +30,15 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(TS* u, long long ldu,
     float sum = 0.0f;
     for (int v = threadIdx.x; v < V; v += blockDim.x) sum += expf(ld_f(row + v) - mx);
     sum = block_reduce(sum, false, sh);
+    // a label outside [0, V) is never used as an index: the frame's loss term becomes NaN and its row p without a one-hot
     const int lab = labels[m];
+    const bool lab_ok = (unsigned)lab < (unsigned)V;
     const float inv = 1.0f / sum;
-    if (threadIdx.x == 0) row_loss[m] = s * (logf(sum) + mx - ld_f(row + lab));
+    if (threadIdx.x == 0) row_loss[m] = lab_ok ? s * (logf(sum) + mx - ld_f(row + lab)) : __builtin_nanf("");
     __syncthreads();                                   // the label's logit is read before it is overwritten
     for (int v = threadIdx.x; v < V; v += blockDim.x) {
         float p = expf(ld_f(row + v) - mx) * inv;
-        st_f(row + v, s * (p - (v == lab ? 1.0f : 0.0f)));
+        st_f(row + v, s * (p - ((lab_ok && v == lab) ? 1.0f : 0.0f)));
     }
 }
 
@@ -85,10 +87,11 @@ __global__ __launch_bounds__(NT) void softmax_rows_bf16_regs_kernel(bf16_t* u, l
     }
     sum = block_reduce(sum, false, sh);
     const int lab = labels[m];
+    const bool lab_ok = (unsigned)lab < (unsigned)V;   // (as in the general kernel: an out-of-range label gives a NaN loss term)
     const float sinv = s / sum;
-    if (threadIdx.x == 0) row_loss[m] = s * (logf(sum) + mx - bf2f(row[lab]));
+    if (threadIdx.x == 0) row_loss[m] = lab_ok ? s * (logf(sum) + mx - bf2f(row[lab])) : __builtin_nanf("");
     __syncthreads();                                   // the label's logit is read before the row is overwritten
-    const int labc = lab >> 3;                         // the one chunk whose output also carries the -s of the one-hot
+    const int labc = lab_ok ? lab >> 3 : -1;           // the one chunk whose output also carries the -s of the one-hot
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
         const int c = threadIdx.x + NT * i;

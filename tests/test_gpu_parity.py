@@ -201,6 +201,30 @@ def test_abandoned_wait_is_reported_in_band_and_recovered_from():
         lrn.close()
 
 
+@pytest.mark.parametrize("V,mode", [(8000, 1), (70000, 1), (300, 0)])
+def test_out_of_range_label_gives_nan_loss_and_no_stray_access(V, mode):
+    # a label outside [0, V) must never be used as an index: the loss turns NaN, every other frame's row is untouched
+    import torch
+    from paper_1904_04956_amd.harness import Learner
+    dims = dict(T=2, B=5, D=8, H=8, L=1, P=8, V=V)
+    dm, theta, x, labels = make_problem(dims, mode, 86, 4.0)
+    lrn = Learner(mode=mode, **dims)
+    try:
+        lrn.set_theta(theta); lrn.set_batch(x, labels)
+        lrn.calgrad(); lrn.check_status()
+        good_dz = lrn.dz.float().cpu().numpy().copy()
+        assert np.isfinite(lrn.loss_value())
+        bad = labels.copy(); bad[1, 3] = V + 12345; bad[0, 0] = -7
+        lrn.labels.copy_(torch.from_numpy(bad))
+        lrn.calgrad(); lrn.check_status()
+        assert np.isnan(lrn.loss_value())
+        dz = lrn.dz.float().cpu().numpy()
+        ok = np.ones((2, 5), dtype=bool); ok[1, 3] = False; ok[0, 0] = False
+        assert np.array_equal(dz[ok], good_dz[ok]) and np.all(np.isfinite(dz))
+    finally:
+        lrn.close()
+
+
 def test_persistent_and_stepwise_paths_agree():
     from paper_1904_04956_amd.harness import Learner
     dims = dict(T=7, B=70, D=48, H=256, L=2, P=32, V=150)
