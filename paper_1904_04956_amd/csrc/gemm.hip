@@ -1040,6 +1040,22 @@ GemmPlan make_plan(const GemmDesc& d, bool allow_r) {
             // Enough 256x128 tiles to put two on (nearly) every CU: the tile that moves 3/4 of the operand bytes of
             // 128x128 per flop, and the only one whose loop keeps the matrix cores above half of their rate.
             if (tr >= 480) { p.tile = GEMM_TILE_256X128; return p; }
+            // Fewer tiles than that but a long contraction next to a narrow output (the softmax layer's input gradient
+            // at large batch): the same tile, split along K into the smallest number of parts that fills whole
+            // rounds of 512 resident workgroups to 90 %, if every part keeps 64 slabs and the float partial tiles
+            // stay below an eighth of the operand bytes.
+            if (tr >= 128 && d.nseg == 1 && d.partial && !d.rowsum) {
+                const int slabs = d.seg[0].K / 64;
+                for (int s = 1; s <= 8; ++s) {
+                    const double rounds = (double)tr * s / 512.0;
+                    const double eff = rounds / (double)(long long)(rounds + 0.999999);
+                    if (eff < 0.9 || slabs / s < 64) continue;
+                    const size_t need = s > 1 ? (size_t)s * batch * ((size_t)d.M * d.N + d.M) * sizeof(float) : 0;
+                    if (s > 1 && ((long long)16 * s * d.N > d.seg[0].K || need > d.partial_bytes)) break;
+                    p.tile = GEMM_TILE_256X128; p.splits = s; p.partial_bytes = need;
+                    return p;
+                }
+            }
         }
         // A handful of large tiles and a very long contraction (the softmax layer's input gradient, dA W form): the
         // 256x256 tile, which moves half the operand bytes of 128x128 per flop, split along K over up to one
