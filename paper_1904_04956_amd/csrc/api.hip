@@ -238,11 +238,13 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     c->nparam = off;
     // workspace layout
     const size_t M = (size_t)c->M, B = (size_t)c->B, e = c->esz;
+    const size_t Br = (B + 31) / 32 * 32, Mr = (size_t)c->T * Br;      // rows rounded up to whole batch tiles
     size_t w = 0;
     for (int l = 0; l < c->L; ++l) { c->wY.push_back(w); w += up256(M * 2 * H * e); }
     for (int l = 0; l < c->L; ++l) {
-        c->wG.push_back(w); w += up256(M * 8 * H * e);
-        c->wC.push_back(w); w += up256(M * 2 * H * 4);
+        // (whole 32-row batch tiles: the persistent kernels keep these two as per-lane records)
+        c->wG.push_back(w); w += up256(Mr * 8 * H * e);
+        c->wC.push_back(w); w += up256(Mr * 2 * H * 4);
     }
     c->wAX = w;      w += up256(M * 8 * H * 4);
     c->wPRE = w;     w += up256(2 * B * 4 * H * 4);
@@ -250,7 +252,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     c->wDY[0] = w;   w += up256(M * 2 * H * e);
     c->wDY[1] = w;   w += up256(M * 2 * H * e);
     c->wDH = w;      w += up256(2 * B * H * 4);
-    c->wDC = w;      w += up256(2 * B * H * 4);
+    c->wDC = w;      w += up256(2 * Br * H * 4);
     c->wLOGITS = w;  w += up256(M * (size_t)c->V * e);
     c->wROWLOSS = w; w += up256(M * 4);
     // A feature width that is not a whole number of tiles (the paper's 260) would put the first layer's two

@@ -42,8 +42,8 @@ struct RecFwdArgs {
     const float* ax;              // W_x x + b for every frame, [M][8H]
     unsigned short* y;            // layer output h, [M][2H]
     unsigned short* hx;           // h again in exchange order, [T][2][tiles][H/16][2][32][8]; pre-filled with 0xFFFF in sentinel mode
-    unsigned short* gates;        // gate activations for rec_bwd_kernel only, [M][2][H][4 gates] (not the per-frame path's [M][8H])
-    float* c;                     // cell state, [M][2H]
+    unsigned short* gates;        // gate activations for rec_bwd_kernel only, as per-lane records [T][2][tiles][H/32][2][256] 16-byte words (not the per-frame path's [M][8H])
+    float* c;                     // cell states, records [T][2][tiles][H/32][256] of four floats; both sized for whole 32-row tiles
     unsigned* cnt;                // [2*nbg][tiles_per_group] counters, zero before the launch
     unsigned* abort_word;         // raised when a wait ran out of time
     unsigned long long limit_ticks;   // wait limit in ticks of the 100 MHz wall clock
@@ -56,11 +56,11 @@ struct RecFwdArgs {
 struct RecBwdArgs {
     const unsigned short* uht[2]; // U_h^T per direction, [H][4H]
     const unsigned short* dy;     // dE/dh from above, [M][2H]
-    const unsigned short* gates;  // as rec_fwd_kernel wrote them, [M][2][H][4 gates]
-    const float* c;               // [M][2H]
+    const unsigned short* gates;  // as rec_fwd_kernel wrote them (per-lane records)
+    const float* c;               // likewise
     unsigned short* da;           // dE/da, [M][8H]
     unsigned short* dax;          // dE/da again in exchange order, [T][2][tiles][4H/16][2][32][8]; pre-filled with 0xFFFF in sentinel mode
-    float* dc;                    // carried dE/dc, [2][B][H]
+    float* dc;                    // carried dE/dc, records [2][tiles][H/32][256] of four floats (whole 32-row tiles)
     unsigned* cnt;
     unsigned* abort_word;
     unsigned long long limit_ticks;

@@ -200,6 +200,14 @@ __device__ __forceinline__ void load_chunks_cached(uint4 (&frag)[NQ], const bf16
 // Element offset of column c (within a direction), row r of a tile, in the exchange order.
 __device__ __forceinline__ unsigned xoff(int c, int r) { return (unsigned)((c >> 3) * 256 + r * 8 + (c & 7)); }
 
+// Saved activations of the persistent kernels ("records"): the forward kernel's lane (workgroup of unit slice u, thread
+// tid) owns four cells of a (frame, direction, batch tile) and the backward kernel's lane of the same ids owns the same
+// four, so what one saves for the other is indexed [frame][direction][tile][unit slice][word][thread] in 16-byte
+// words: a lane reads back exactly what it wrote, with one wide access per word instead of one per cell.
+__device__ __forceinline__ size_t rec_index(int t, int d, int tile, int NT, int NU, int u) {
+    return ((size_t)(t * 2 + d) * NT + tile) * NU + u;
+}
+
 // Number of 32-row batch tiles of this workgroup's group that lie inside the batch.
 __device__ __forceinline__ int tiles_in_batch(int bg, int tiles_per_group, int B) {
     const int first = bg * tiles_per_group * 32;
@@ -263,9 +271,7 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     // Register e is batch row rb + re(e) of the tile: rb per thread, re(e) a compile-time constant.
     const int rb = 2 * EPT * wave + 4 * lh;
     auto re = [](int e) { return 8 * (e >> 2) + (e & 3); };
-    const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // into [.][2H] tensors (h, c)
     const unsigned o8b = (unsigned)(rb * 8 * H + d * 4 * H + j); // into the row-major [.][8H] tensor (a_x)
-    const unsigned ogb = (unsigned)(rb * 8 * H + (d * H + j) * 4); // into the saved gates, [.][2][H][4]
     const int NT = (B + 31) / 32;                        // 32-row tiles of the batch
     constexpr int XH = H / 16 * XPAIR;                   // exchange elements per (frame, direction, tile)
     const unsigned ohp = (unsigned)(wave * (KW / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
@@ -280,14 +286,16 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         const int tp = d ? T - n : n - 1;
         const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
         const float* axb = a.ax + ((size_t)t * B + b0) * 8 * H;
-        const float* cpb = a.c + ((size_t)(n > 0 ? tp : t) * B + b0) * 2 * H;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             const bool ok = FULL || b0 + rb + re(e) < B;
 #pragma unroll
             for (int g = 0; g < 4; ++g) ax[e][g] = ok ? axb[o8b + (unsigned)((re(e) * 8 + g) * H)] : 0.0f;
-            cp[e] = (ok && n > 0 && ntl > 1) ? cpb[o2b + (unsigned)(re(e) * 2 * H)] : 0.0f;   // (one tile: c stays in registers)
         }
+        // the previous cell state of this lane's four cells is one 16-byte word of the saved records (one tile: c stays in registers)
+        float4 c4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (n > 0 && ntl > 1) c4 = reinterpret_cast<const float4*>(a.c)[rec_index(tp, d, b0 >> 5, NT, NU, u) * 256 + threadIdx.x];
+        cp[0] = c4.x; cp[1] = c4.y; cp[2] = c4.z; cp[3] = c4.w;
     };
 
     const int nitems = T * ntl;
@@ -315,16 +323,15 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
     auto flush_tail = [&]() __attribute__((always_inline)) {
         if (!tail.have) return;
         tail.have = false;
-        float* cb = a.c + ((size_t)tail.t * B + tail.b0) * 2 * H;
         bf16_t* yb = a.y + ((size_t)tail.t * B + tail.b0) * 2 * H;
-        bf16_t* gb = a.gates + ((size_t)tail.t * B + tail.b0) * 8 * H;
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            if (FULL || tail.b0 + rb + re(e) < B) {
-                cb[o2b + (unsigned)(re(e) * 2 * H)] = tail.cn[e];
-                // the four gate activations of a unit are one 8-byte word: [frame row][direction][unit][gate]
-                *reinterpret_cast<uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) = tail.g[e];
-            }
+        // What the backward kernel needs of this lane's four cells goes out as the lane's record: three 16-byte words
+        // (gates of cells 0-1, gates of cells 2-3, the four cell states), each word array contiguous over the workgroup.
+        {
+            const size_t r = rec_index(tail.t, d, tail.b0 >> 5, NT, NU, u);
+            uint4* g4 = reinterpret_cast<uint4*>(a.gates) + r * 2 * 256 + threadIdx.x;
+            g4[0] = make_uint4(tail.g[0].x, tail.g[0].y, tail.g[1].x, tail.g[1].y);
+            g4[256] = make_uint4(tail.g[2].x, tail.g[2].y, tail.g[3].x, tail.g[3].y);
+            reinterpret_cast<float4*>(a.c)[r * 256 + threadIdx.x] = make_float4(tail.cn[0], tail.cn[1], tail.cn[2], tail.cn[3]);
         }
         const int lane_ = threadIdx.x & 63;
         const int xrow_ = 2 * EPT * (int)(threadIdx.x >> 6) + 4 * (lane_ >> 5) + ((lane_ >> 3) & 3);
@@ -544,9 +551,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     // per-thread 32-bit element offsets, added to per-item uniform bases (as in the forward kernel)
     const int rb = 2 * EPT * wave + 4 * lh;              // register e is batch row rb + re(e) of the tile
     auto re = [](int e) { return 8 * (e >> 2) + (e & 3); };
-    const unsigned o1b = (unsigned)(rb * H + j);                 // into [.][H] (carried dE/dc),
-    const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // [.][2H] (c, dy)
-    const unsigned ogb = (unsigned)(rb * 8 * H + (d * H + j) * 4); // and the saved gates, [.][2][H][4]
+    const unsigned o2b = (unsigned)(rb * 2 * H + d * H + j);     // into [.][2H] (dy)
     const int NT = (B + 31) / 32;
     constexpr int XA = 4 * H / 16 * XPAIR;               // exchange elements per (frame, direction, tile)
     const unsigned oap = (unsigned)(wave * (KWB / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
@@ -560,20 +565,26 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         const int tp = d ? T - n : n - 1;
         const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
         const size_t m0 = (size_t)t * B + b0;
-        const bf16_t* gb = a.gates + m0 * 8 * H;
-        const float* cb = a.c + m0 * 2 * H;
-        const float* cpb = a.c + ((size_t)(n > 0 ? tp : t) * B + b0) * 2 * H;
         const bf16_t* dyb = a.dy + m0 * 2 * H;
-        const float* dcb = a.dc + ((size_t)d * B + b0) * H;
+        // the lane's records (see rec_index): gates of its four cells, their cell states, those of the frame visited before
+        const size_t r = rec_index(t, d, b0 >> 5, NT, NU, u);
+        const uint4* g4 = reinterpret_cast<const uint4*>(a.gates) + r * 2 * 256 + threadIdx.x;
+        const uint4 g01 = g4[0], g23 = g4[256];
+        float4 c4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f), cp4 = c4, dc4 = c4;
+        if (ntl > 1 || item == 0) c4 = reinterpret_cast<const float4*>(a.c)[r * 256 + threadIdx.x];   // (one tile: the c of this frame was the item before's c_prev)
+        if (n > 0) cp4 = reinterpret_cast<const float4*>(a.c)[rec_index(tp, d, b0 >> 5, NT, NU, u) * 256 + threadIdx.x];
+        if (n < T - 1 && ntl > 1) dc4 = reinterpret_cast<const float4*>(a.dc)[((size_t)(d * NT + (b0 >> 5)) * NU + u) * 256 + threadIdx.x];   // (one tile: carried in registers)
+        static_assert(EPT == 4, "a record holds four cells");
+        in.g[0] = make_uint2(g01.x, g01.y); in.g[1] = make_uint2(g01.z, g01.w);
+        in.g[2] = make_uint2(g23.x, g23.y); in.g[3] = make_uint2(g23.z, g23.w);
+        in.c[0] = c4.x; in.c[1] = c4.y; in.c[2] = c4.z; in.c[3] = c4.w;
+        in.cp[0] = cp4.x; in.cp[1] = cp4.y; in.cp[2] = cp4.z; in.cp[3] = cp4.w;
+        in.dcr[0] = dc4.x; in.dcr[1] = dc4.y; in.dcr[2] = dc4.z; in.dcr[3] = dc4.w;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             const bool ok = FULL || b0 + rb + re(e) < B;
-            const unsigned o2 = o2b + (unsigned)(re(e) * 2 * H);
-            in.g[e] = ok ? *reinterpret_cast<const uint2*>(gb + (ogb + (unsigned)(re(e) * 8 * H))) : make_uint2(0u, 0u);
-            in.c[e] = (ok && (ntl > 1 || item == 0)) ? cb[o2] : 0.0f;   // (one tile: the c of this frame was the item before's c_prev)
-            in.cp[e] = (ok && n > 0) ? cpb[o2] : 0.0f;
-            in.dy[e] = ok ? dyb[o2] : (bf16_t)0;
-            in.dcr[e] = (ok && n < T - 1 && ntl > 1) ? dcb[o1b + (unsigned)(re(e) * H)] : 0.0f;   // (one tile: carried in registers)
+            in.dy[e] = ok ? dyb[o2b + (unsigned)(re(e) * 2 * H)] : (bf16_t)0;
+            if (!ok) { in.g[e] = make_uint2(0u, 0u); in.c[e] = 0.0f; in.cp[e] = 0.0f; in.dcr[e] = 0.0f; }
         }
     };
 
@@ -746,18 +757,14 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         if (SENTINEL) lds_barrier();
         else signal_counter(cnt + i);
         // row-major dE/da for the weight- and input-gradient products, and the carried dE/dc
-        float* dcb = a.dc + ((size_t)d * B + b0) * H;
         bf16_t* dab = a.da + ((size_t)t * B + b0) * 8 * H;
         if (xok) {
             bf16_t* pr = dab + ((unsigned)xrow * (unsigned)(8 * H) + (unsigned)(d * 4 * H) + xcol);
             *reinterpret_cast<uint4*>(pr) = cga;
             *reinterpret_cast<uint4*>(pr + H) = cgb;
         }
-        if (ntl > 1) {
-#pragma unroll
-            for (int e = 0; e < EPT; ++e)
-                if (FULL || b0 + rb + re(e) < B) dcb[o1b + (unsigned)(re(e) * H)] = dcf[e];
-        }
+        if (ntl > 1)                                      // carried dE/dc of the lane's four cells: one 16-byte word
+            reinterpret_cast<float4*>(a.dc)[((size_t)(d * NT + (b0 >> 5)) * NU + u) * 256 + threadIdx.x] = make_float4(dcf[0], dcf[1], dcf[2], dcf[3]);
         // next item's inputs; with one tile per workgroup its carried dE/dc is the one just computed
 #pragma unroll
         for (int e = 0; e < EPT; ++e) { dccarry[e] = dcf[e]; ccarry[e] = cur.cp[e]; }
