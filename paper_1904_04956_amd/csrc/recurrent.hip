@@ -84,10 +84,14 @@ __device__ __forceinline__ void st_coh_8B(bf16_t* p, const uint2& v) {
     __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), (unsigned long long)v.x | ((unsigned long long)v.y << 32),
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// One 16-byte store with the cache policy of an agent-scope atomic store (write-through to L2: sc1), written in assembly
+// because atomics stop at 8 bytes and a store instruction costs the memory pipeline the same whatever its width.  The
+// protocol needs no atomicity beyond each 16-bit element's, which every aligned store gives.  (The compiler does not
+// count this store in its vmcnt bookkeeping; its own waits then only wait for more than they need.)
+typedef unsigned int u32x4s_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void st_coh_16B(bf16_t* p, const uint4& v) {
-    unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
-    __hip_atomic_store(q, (unsigned long long)v.x | ((unsigned long long)v.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(q + 1, (unsigned long long)v.z | ((unsigned long long)v.w << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const u32x4s_t w = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(w) : "memory");
 }
 __device__ __forceinline__ uint4 ld_coh_16B(const bf16_t* p) {
     const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
@@ -286,6 +290,8 @@ __global__ __launch_bounds__(64 * NW) void rec_fwd_kernel(RecFwdArgs a) {
         const int tp = d ? T - n : n - 1;
         const int b0 = (gm.bg * a.tiles_per_group + i) * 32;
         const float* axb = a.ax + ((size_t)t * B + b0) * 8 * H;
+        // (a_x fetched as 16-byte pieces and transposed through LDS, a quarter of these loads, was measured: no gain with
+        // one tile per workgroup, where the loads hide under the exchange wait, and slower with several)
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             const bool ok = FULL || b0 + rb + re(e) < B;
@@ -557,7 +563,12 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
     const unsigned oap = (unsigned)(wave * (KWB / 16) * XPAIR + lane * 8);   // this lane's 16 bytes of each chunk pair
 
     // Saved activations of an item, loaded one item ahead (raw bf16 for the gates and dy).
-    struct Inputs { uint2 g[EPT]; bf16_t dy[EPT]; float c[EPT], cp[EPT], dcr[EPT]; };   // g: (i, f), (g, o) as bf16 pairs
+    // dy of a wavefront's cells is eight rows of 32 units: 512 contiguous-by-row bytes.  With one tile per workgroup
+    // 32 lanes fetch it as one 16-byte piece each (dyr) and the wavefront spreads it through LDS at the start of the item
+    // (one vector-memory instruction instead of four); with several tiles each lane loads its four values (see the
+    // forward kernel's a_x for why).
+    constexpr bool WIDE_DY = !MULTI;
+    struct Inputs { uint2 g[EPT]; bf16_t dy[EPT]; uint4 dyr; float c[EPT], cp[EPT], dcr[EPT]; };   // g: (i, f), (g, o) as bf16 pairs
     auto issue_inputs = [&](int item, Inputs& in) {
         const int ni = item / ntl, i = item - ni * ntl;
         const int n = T - 1 - ni;
@@ -574,6 +585,11 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         if (ntl > 1 || item == 0) c4 = reinterpret_cast<const float4*>(a.c)[r * 256 + threadIdx.x];   // (one tile: the c of this frame was the item before's c_prev)
         if (n > 0) cp4 = reinterpret_cast<const float4*>(a.c)[rec_index(tp, d, b0 >> 5, NT, NU, u) * 256 + threadIdx.x];
         if (n < T - 1 && ntl > 1) dc4 = reinterpret_cast<const float4*>(a.dc)[((size_t)(d * NT + (b0 >> 5)) * NU + u) * 256 + threadIdx.x];   // (one tile: carried in registers)
+        if constexpr (WIDE_DY) {                         // piece lane % 32: row (lane % 32) / 4 of the wavefront's eight, units 8 (lane % 4) .. + 7
+            const int row = 2 * EPT * wave + (l32 >> 2);
+            in.dyr = make_uint4(0u, 0u, 0u, 0u);
+            if (FULL || b0 + row < B) in.dyr = *reinterpret_cast<const uint4*>(dyb + (size_t)row * 2 * H + d * H + u * 32 + (l32 & 3) * 8);
+        }
         static_assert(EPT == 4, "a record holds four cells");
         in.g[0] = make_uint2(g01.x, g01.y); in.g[1] = make_uint2(g01.z, g01.w);
         in.g[2] = make_uint2(g23.x, g23.y); in.g[3] = make_uint2(g23.z, g23.w);
@@ -583,7 +599,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             const bool ok = FULL || b0 + rb + re(e) < B;
-            in.dy[e] = ok ? dyb[o2b + (unsigned)(re(e) * 2 * H)] : (bf16_t)0;
+            if constexpr (!WIDE_DY) in.dy[e] = ok ? dyb[o2b + (unsigned)(re(e) * 2 * H)] : (bf16_t)0;
             if (!ok) { in.g[e] = make_uint2(0u, 0u); in.c[e] = 0.0f; in.cp[e] = 0.0f; in.dcr[e] = 0.0f; }
         }
     };
@@ -612,6 +628,16 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         float dh[EPT];
 #pragma unroll
         for (int e = 0; e < EPT; ++e) dh[e] = 0.0f;
+        bf16_t dyv[EPT];
+        if constexpr (WIDE_DY) {
+            bf16_t* dys = reinterpret_cast<bf16_t*>(lds + NW * 4 * 64 * 4 + NW * 512) + wave * 256;   // 512 bytes per wavefront: [row][unit]
+            if (lane < 32) reinterpret_cast<uint4*>(dys)[lane] = cur.dyr;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) dyv[e] = dys[(4 * lh + e) * 32 + l32];
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) dyv[e] = cur.dy[e];
+        }
         if (n < T - 1) {
             const int row = b0 + l32;
             const bool valid = FULL || row < B;
@@ -712,7 +738,7 @@ __global__ __launch_bounds__(64 * NW) void rec_bwd_kernel(RecBwdArgs a) {
         for (int e = 0; e < EPT; ++e) {
             const float gi = bf2f((bf16_t)(cur.g[e].x & 0xFFFFu)), gf = bf2f((bf16_t)(cur.g[e].x >> 16));
             const float gg = bf2f((bf16_t)(cur.g[e].y & 0xFFFFu)), go = bf2f((bf16_t)(cur.g[e].y >> 16));
-            const float dht = dh[e] + bf2f(cur.dy[e]) + poison;
+            const float dht = dh[e] + bf2f(dyv[e]) + poison;
             const float tc = fast_tanh(cthis[e]);
             const float dc = dht * go * (1.0f - tc * tc) + dcr[e];
             const float da_o = dht * tc * go * (1.0f - go);
@@ -876,7 +902,7 @@ hipError_t run_fwd(const RecFwdArgs& a, int grid, hipStream_t st, bool* launched
 }
 template <int NW, int KW, bool S, bool FULL, bool MULTI>
 hipError_t run_bwd_m(const RecBwdArgs& a, int grid, hipStream_t st, bool* launched) {
-    const size_t lds = (size_t)NW * 4 * 64 * 16 + (size_t)NW * 2048;   // partial sums; regrouping of dE/da, 2 KB per wavefront
+    const size_t lds = (size_t)NW * 4 * 64 * 16 + (size_t)NW * 2048 + (size_t)NW * 512;   // partial sums; regrouping of dE/da, 2 KB per wavefront; spreading dy, 512 bytes per wavefront
     bool fits = false;
     static thread_local FitCache cache{false, 0};
     hipError_t e = prepare(rec_bwd_kernel<NW, KW, S, FULL, MULTI>, 64 * NW, lds, grid, &cache, &fits);
