@@ -12,6 +12,7 @@ Prints ONE JSON line:
   roofline         the kernel that takes the largest share of the step, by kernel name, against the
                    bf16 MFMA peak; roofline_gemm: the plain product class with the largest share;
   adpsgd_mix ...   the streaming kernels against HBM bandwidth;
+  other_workloads  the same step on the large-batch, 6x1024 and 6x512 workloads, briefly (8 timed steps each);
   cpu_baseline     the float64 oracle timed on this machine's host cores on the same workload.
 HBM traffic figures ("traffic") are read from profiles/hbm_traffic_<workload>.txt, which records the
 hash of the kernel sources it was measured with; they are null when the sources have changed since.
@@ -114,6 +115,8 @@ def main():
     ap.add_argument("--rec-sync", type=int, default=-1, help="exchange protocol of the persistent kernels (library default if < 0)")
     ap.add_argument("--rec-path", type=int, default=0, help="1 = one launch per frame")
     ap.add_argument("--mix-replicas", type=int, default=16, help="replicas of the separate adpsgd_mix measurement")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other workloads (large batch, 6x1024, 6x512) reported under other_workloads")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="first copy 1 GiB three times with a plain copy kernel (reference for HBM counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -287,6 +290,45 @@ def main():
                            "unit": "GB/s", "frac": pair_bytes / (pair_ms * 1e-3) / PEAK_HBM, "bytes_per_launch": pair_bytes,
                            "note": "one pass for both replicas' sgd_step and their adpsgd_mix (lr = 0 here so the weights stay put)"}
     lrn.close()
+    del lrn, nb_theta, nb_shadow, nb_grad, masters, shadows
+    torch.cuda.empty_cache()
+
+    # ---- the other workloads, briefly: the same step (forward .. adpsgd_mix with a neighbour), 3 warm-up + 8 timed steps ----
+    if not args.no_other_workloads and args.workload == "paper4x512" and args.batch == 0:
+        others = {}
+        for name in ("largebatch", "wide6x1024", "paper6x512"):
+            ow = inputs.WORKLOADS[name]
+            od = ow.dims()
+            ol = Learner(mode=ow.mode, **od)
+            ol.set_theta(inputs.make_theta(ol.n, ow.seed, bf16=ow.mode == 1))
+            ox, olab = inputs.make_batch(od["T"], od["B"], od["D"], od["V"], ow.seed, bf16=ow.mode == 1)
+            ol.set_batch(ox, olab)
+            onb, onbs = ol.theta.clone(), ol.shadow.clone()
+
+            def ostep():
+                ol.calgrad()
+                ol.apply(ow.lr)
+                bl.adpsgd_mix([ol.theta, onb], [ol.shadow, onbs], ol.n, 2, [1, 0])
+                ol.weights_changed()
+
+            for _ in range(3):
+                ostep()
+            ol.check_status()
+            t0 = time.perf_counter()
+            for _ in range(8):
+                ostep()
+            torch.cuda.synchronize()
+            odt = (time.perf_counter() - t0) / 8
+            ol.check_status()
+            ofpf = flop_per_frame(od["D"], od["H"], od["L"], od["P"], od["V"])
+            others[name] = {"workload": f"{od['L']}x{od['H']} BLSTM, D={od['D']}, T={od['T']}, B={od['B']}, P={od['P']}, V={od['V']}",
+                            "ms_per_step": 1e3 * odt, "frames_per_s": od["T"] * od["B"] / odt,
+                            "pct_of_mfma_peak": 100.0 * od["T"] * od["B"] / odt * ofpf / PEAK_BF16_MFMA, "steps": 8, "warmup": 3,
+                            "final_loss": ol.loss_value()}
+            ol.close()
+            del ol, onb, onbs
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
 
     # ---- the oracle on this machine's host cores: the same workload, whole batch, best of three steps ------------
     if not args.no_cpu_baseline:
