@@ -97,35 +97,52 @@ __global__ __launch_bounds__(UPD_THREADS) void sgd_mix_pair_kernel(float* __rest
                                                                    float* __restrict__ vi, float* __restrict__ vj,
                                                                    unsigned short* __restrict__ si, unsigned short* __restrict__ sj,
                                                                    size_t n, float lr, float mu) {
+    // one contiguous span of PAIR_U * UPD_THREADS 16-byte words per workgroup, all loads of a span before its first store
+    constexpr int PAIR_U = 2;
     const size_t n4 = n / 4;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        float4 a = reinterpret_cast<const float4*>(ti)[i];
-        float4 b = reinterpret_cast<const float4*>(tj)[i];
-        float4 ga = reinterpret_cast<const float4*>(gi)[i];
-        float4 gb = reinterpret_cast<const float4*>(gj)[i];
-        if (MOM) {
-            const float4 va = reinterpret_cast<const float4*>(vi)[i];
-            const float4 vb = reinterpret_cast<const float4*>(vj)[i];
-            ga.x = mu * va.x + ga.x; ga.y = mu * va.y + ga.y; ga.z = mu * va.z + ga.z; ga.w = mu * va.w + ga.w;
-            gb.x = mu * vb.x + gb.x; gb.y = mu * vb.y + gb.y; gb.z = mu * vb.z + gb.z; gb.w = mu * vb.w + gb.w;
-            reinterpret_cast<float4*>(vi)[i] = ga;
-            reinterpret_cast<float4*>(vj)[i] = gb;
+    const size_t base = (size_t)blockIdx.x * PAIR_U * UPD_THREADS + threadIdx.x;
+    f32x4_t a[PAIR_U], b[PAIR_U], ga[PAIR_U], gb[PAIR_U], va[PAIR_U], vb[PAIR_U];
+#pragma unroll
+    for (int k = 0; k < PAIR_U; ++k) {
+        const size_t i = base + (size_t)k * UPD_THREADS;
+        if (i < n4) {
+            a[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(ti) + i);
+            b[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(tj) + i);
+            ga[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(gi) + i);
+            gb[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(gj) + i);
+            if (MOM) {
+                va[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(vi) + i);
+                vb[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(vj) + i);
+            }
         }
-        a.x -= lr * ga.x; a.y -= lr * ga.y; a.z -= lr * ga.z; a.w -= lr * ga.w;
-        b.x -= lr * gb.x; b.y -= lr * gb.y; b.z -= lr * gb.z; b.w -= lr * gb.w;
-        float4 m;
-        m.x = 0.5f * (a.x + b.x); m.y = 0.5f * (a.y + b.y); m.z = 0.5f * (a.z + b.z); m.w = 0.5f * (a.w + b.w);
-        reinterpret_cast<float4*>(ti)[i] = m;
-        reinterpret_cast<float4*>(tj)[i] = m;
-        if (SHADOW) { const uint2 q = pack4(m); reinterpret_cast<uint2*>(si)[i] = q; reinterpret_cast<uint2*>(sj)[i] = q; }
+    }
+#pragma unroll
+    for (int k = 0; k < PAIR_U; ++k) {
+        const size_t i = base + (size_t)k * UPD_THREADS;
+        if (i < n4) {
+            if (MOM) {
+                ga[k] = mu * va[k] + ga[k];
+                gb[k] = mu * vb[k] + gb[k];
+                __builtin_nontemporal_store(ga[k], reinterpret_cast<f32x4_t*>(vi) + i);
+                __builtin_nontemporal_store(gb[k], reinterpret_cast<f32x4_t*>(vj) + i);
+            }
+            const f32x4_t x = a[k] - lr * ga[k], y = b[k] - lr * gb[k];
+            const f32x4_t m = 0.5f * (x + y);
+            __builtin_nontemporal_store(m, reinterpret_cast<f32x4_t*>(ti) + i);
+            __builtin_nontemporal_store(m, reinterpret_cast<f32x4_t*>(tj) + i);
+            if (SHADOW) {
+                u32x2_t q; q[0] = pack_bf2(m[0], m[1]); q[1] = pack_bf2(m[2], m[3]);
+                __builtin_nontemporal_store(q, reinterpret_cast<u32x2_t*>(si) + i);
+                __builtin_nontemporal_store(q, reinterpret_cast<u32x2_t*>(sj) + i);
+            }
+        }
     }
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
         const size_t i = n4 * 4 + threadIdx.x;
-        float ga = gi[i], gb = gj[i];
-        if (MOM) { ga = mu * vi[i] + ga; vi[i] = ga; gb = mu * vj[i] + gb; vj[i] = gb; }
-        const float a = ti[i] - lr * ga, b = tj[i] - lr * gb;
-        const float m = 0.5f * (a + b);
+        float ga1 = gi[i], gb1 = gj[i];
+        if (MOM) { ga1 = mu * vi[i] + ga1; vi[i] = ga1; gb1 = mu * vj[i] + gb1; vj[i] = gb1; }
+        const float a1 = ti[i] - lr * ga1, b1 = tj[i] - lr * gb1;
+        const float m = 0.5f * (a1 + b1);
         ti[i] = m; tj[i] = m;
         if (SHADOW) { si[i] = f2bf(m); sj[i] = f2bf(m); }
     }
@@ -136,8 +153,12 @@ __global__ __launch_bounds__(UPD_THREADS) void sgd_mix_pair_kernel(float* __rest
 template <bool SHADOW>
 __global__ __launch_bounds__(UPD_THREADS) void sync_average_kernel(ReplicaSet p, size_t n, float inv_r) {
     const size_t n4 = n / 4;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    // a workgroup owns one contiguous span of SYNC_U * UPD_THREADS 16-byte words of every replica
+    constexpr int SYNC_U = 2;
+#pragma unroll
+    for (int k = 0; k < SYNC_U; ++k) {
+        const size_t i = ((size_t)blockIdx.x * SYNC_U + k) * UPD_THREADS + threadIdx.x;
+        if (i >= n4) break;
         // four replicas' loads in flight at a time, added in index order
         f32x4_t acc = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p.t[0]) + i);
         int r = 1;
@@ -208,7 +229,8 @@ hipError_t launch_mix(const MixPairs& p, size_t n, hipStream_t st) {
 hipError_t launch_sgd_mix_pair(float* ti, float* tj, const float* gi, const float* gj, float* vi, float* vj,
                                unsigned short* si, unsigned short* sj, size_t n, float lr, float mu, hipStream_t st) {
     if (n == 0) return hipSuccess;
-    dim3 grid(blocks_for(n / 4, 256 * 16)), block(UPD_THREADS);
+    const size_t spans = (n / 4 + 2 * UPD_THREADS - 1) / (2 * UPD_THREADS);      // (PAIR_U words per thread)
+    dim3 grid((unsigned)(spans < 1 ? 1 : spans)), block(UPD_THREADS);
     const bool mom = (mu != 0.0f), sh = si != nullptr;
     if (sh && mom) hipLaunchKernelGGL((sgd_mix_pair_kernel<true, true>), grid, block, 0, st, ti, tj, gi, gj, vi, vj, si, sj, n, lr, mu);
     else if (sh) hipLaunchKernelGGL((sgd_mix_pair_kernel<true, false>), grid, block, 0, st, ti, tj, gi, gj, vi, vj, si, sj, n, lr, mu);
@@ -219,7 +241,8 @@ hipError_t launch_sgd_mix_pair(float* ti, float* tj, const float* gi, const floa
 
 hipError_t launch_sync_average(const ReplicaSet& p, size_t n, hipStream_t st) {
     if (n == 0 || p.R < 1) return hipSuccess;
-    dim3 grid(blocks_for(n / 4, 256 * 16)), block(UPD_THREADS);
+    const size_t spans = (n / 4 + 2 * UPD_THREADS - 1) / (2 * UPD_THREADS);      // (SYNC_U words per thread)
+    dim3 grid((unsigned)(spans < 1 ? 1 : spans)), block(UPD_THREADS);
     const float inv_r = 1.0f / (float)p.R;
     if (p.s[0]) hipLaunchKernelGGL(sync_average_kernel<true>, grid, block, 0, st, p, n, inv_r);
     else hipLaunchKernelGGL(sync_average_kernel<false>, grid, block, 0, st, p, n, inv_r);
