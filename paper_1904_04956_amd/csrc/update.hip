@@ -12,23 +12,39 @@ typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint2 pack4(float4 v) { return make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)); }
 
+constexpr int SGD_U = 2;
 template <bool SHADOW, bool MOM>
 __global__ __launch_bounds__(UPD_THREADS) void sgd_kernel(float* __restrict__ theta, unsigned short* __restrict__ shadow,
                                                           const float* __restrict__ grad, float* __restrict__ vel,
                                                           size_t n, float lr, float mu) {
+    // one contiguous span of SGD_U * UPD_THREADS 16-byte words per workgroup, all loads of a span before its first store
     const size_t n4 = n / 4;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        float4 t = reinterpret_cast<const float4*>(theta)[i];
-        float4 g = reinterpret_cast<const float4*>(grad)[i];
-        if (MOM) {
-            float4 v = reinterpret_cast<const float4*>(vel)[i];
-            g.x = mu * v.x + g.x; g.y = mu * v.y + g.y; g.z = mu * v.z + g.z; g.w = mu * v.w + g.w;
-            reinterpret_cast<float4*>(vel)[i] = g;
+    const size_t base = (size_t)blockIdx.x * SGD_U * UPD_THREADS + threadIdx.x;
+    f32x4_t t[SGD_U], g[SGD_U], v[SGD_U];
+#pragma unroll
+    for (int k = 0; k < SGD_U; ++k) {
+        const size_t i = base + (size_t)k * UPD_THREADS;
+        if (i < n4) {
+            t[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(theta) + i);
+            g[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(grad) + i);
+            if (MOM) v[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(vel) + i);
         }
-        t.x -= lr * g.x; t.y -= lr * g.y; t.z -= lr * g.z; t.w -= lr * g.w;
-        reinterpret_cast<float4*>(theta)[i] = t;
-        if (SHADOW) reinterpret_cast<uint2*>(shadow)[i] = pack4(t);
+    }
+#pragma unroll
+    for (int k = 0; k < SGD_U; ++k) {
+        const size_t i = base + (size_t)k * UPD_THREADS;
+        if (i < n4) {
+            if (MOM) {
+                g[k] = mu * v[k] + g[k];
+                __builtin_nontemporal_store(g[k], reinterpret_cast<f32x4_t*>(vel) + i);
+            }
+            const f32x4_t r = t[k] - lr * g[k];
+            __builtin_nontemporal_store(r, reinterpret_cast<f32x4_t*>(theta) + i);
+            if (SHADOW) {
+                u32x2_t q; q[0] = pack_bf2(r[0], r[1]); q[1] = pack_bf2(r[2], r[3]);
+                __builtin_nontemporal_store(q, reinterpret_cast<u32x2_t*>(shadow) + i);
+            }
+        }
     }
     // tail (n not a multiple of four)
     if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
@@ -208,7 +224,8 @@ unsigned blocks_for(size_t n4, unsigned cap) {
 hipError_t launch_sgd(float* theta, unsigned short* shadow, const float* grad, size_t n, float lr, float mu,
                       float* vel, hipStream_t st) {
     if (n == 0) return hipSuccess;
-    dim3 grid(blocks_for(n / 4, 256 * 16)), block(UPD_THREADS);
+    const size_t spans = (n / 4 + SGD_U * UPD_THREADS - 1) / (SGD_U * UPD_THREADS);
+    dim3 grid((unsigned)(spans < 1 ? 1 : spans)), block(UPD_THREADS);
     const bool mom = (mu != 0.0f);
     if (shadow && mom) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, block, 0, st, theta, shadow, grad, vel, n, lr, mu);
     else if (shadow) hipLaunchKernelGGL((sgd_kernel<true, false>), grid, block, 0, st, theta, shadow, grad, vel, n, lr, mu);
