@@ -175,3 +175,37 @@ def test_pair_and_average_validation():
     odd = (ctypes.c_void_p * 4)(4096, 8196, 12288, 16384)
     assert L.sync_average(odd, None, 16, 4, None) == -4
     assert L.sync_average(ptrs, None, 0, 4, None) == 0
+
+
+def test_bench_flop_counts_match_the_closed_forms():
+    # forward + backward FLOP per frame = 2 (3 MACs - layer 1's input-gradient product): 180.8 M for the 4x512 model,
+    # 256.3 M for the paper's 6x512 model, 866.1 M for 6x1024; the per-class split adds up to the same total
+    import bench
+    assert round(bench.flop_per_frame(260, 512, 4, 256, 32000) / 1e6, 1) == 180.8
+    assert round(bench.flop_per_frame(260, 512, 6, 256, 32000) / 1e6, 1) == 256.3
+    assert round(bench.flop_per_frame(260, 1024, 6, 256, 32000) / 1e6, 1) == 866.1
+    T, B = 21, 256
+    f = bench.flops_by_class(T, B, 260, 512, 4, 256, 32000)
+    total = sum(f[k] for k in ("gemm_input_projection", "gemm_bottleneck", "gemm_logits", "gemm_softmax_bwd", "gemm_wgrad", "gemm_dgrad"))
+    # the recurrent products count T - 1 frames per sequence (the first visited frame has no previous h), forward,
+    # backward and in the weight gradient (which is in gemm_wgrad with T - 1 already)
+    total += f["recurrent_fwd_persistent"] + f["recurrent_bwd_persistent"]
+    per_frame = bench.flop_per_frame(260, 512, 4, 256, 32000)
+    missing = 2 * 3 * (2 * 4 * 512 * 512) * 4 * B          # the frame the recurrent products skip, all three passes, four layers
+    assert total == per_frame * T * B - missing
+
+
+def test_bench_traffic_file_is_keyed_to_the_kernel_sources(tmp_path, monkeypatch):
+    import bench
+    prof = tmp_path / "profiles"
+    prof.mkdir()
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    assert bench.measured_traffic("paper4x512", 256) == {}                       # no file
+    (tmp_path / "paper_1904_04956_amd" / "csrc").mkdir(parents=True)
+    (tmp_path / "paper_1904_04956_amd" / "csrc" / "k.hip").write_text("kernel v1")
+    h = bench.source_hash()
+    (prof / "hbm_traffic_paper4x512.txt").write_text(f"# prose\nsources {h}\nbatch 256\nbytes_per_launch gemm_wgrad 123.0  # note\n")
+    assert bench.measured_traffic("paper4x512", 256) == {"gemm_wgrad": 123.0}
+    assert bench.measured_traffic("paper4x512", 128) == {}                       # another batch size
+    (tmp_path / "paper_1904_04956_amd" / "csrc" / "k.hip").write_text("kernel v2")
+    assert bench.measured_traffic("paper4x512", 256) == {}                       # the sources have changed since
