@@ -2,8 +2,9 @@
 """Benchmark of one learner's training step on one MI355X.
 
 A step is one pass of the whole hot path over one synthetic batch: blstm_forward,
-softmax_xent_fwd_bwd, blstm_backward, sgd_step and one adpsgd_mix with a ring neighbour's
-replica held in the same HBM.  Inputs are resident in HBM before the timed region.
+softmax_xent_fwd_bwd, blstm_backward, the learner's sgd_step and its adpsgd_mix with a ring
+neighbour's replica held in the same HBM (the last two as one pass over the weights: sgd_mix_pair
+without a gradient for the neighbour, bit-identical to the two calls).  Inputs are resident in HBM before the timed region.
 
 Prints ONE JSON line:
   value            frames/s of the whole job (wall clock around K steps, synchronised on both sides);
@@ -161,8 +162,9 @@ def main():
 
     def step():
         lrn.calgrad()
-        lrn.apply(w.lr)
-        bl.adpsgd_mix(masters, shadows, lrn.n, 2, [1, 0])
+        # Eq. 4 for this learner: its own update (Eq. 1c), then the average with the neighbour's replica as it stands,
+        # in one pass over the weights (same bits as sgd_step followed by adpsgd_mix)
+        bl.sgd_mix_pair(lrn.theta, nb_theta, lrn.shadow, nb_shadow, lrn.grad, None, lrn.n, w.lr, lrn.momentum, lrn.velocity, None)
         lrn.weights_changed()
 
     for _ in range(args.warmup):
@@ -191,7 +193,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if bf else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {d['L']}x{d['H']} BLSTM, D={d['D']}, T={T}, B={B}, P={d['P']}, V={d['V']}, "
-                               f"step = forward + softmax-xent + backward + sgd_step + adpsgd_mix with one neighbour replica",
+                               f"step = forward + softmax-xent + backward + sgd_step + adpsgd_mix with one neighbour replica (update and average in one pass)",
                    "global_batch": B, "seq_len": T, "lr": w.lr},
         "step_ms": {"median": statistics.median(each), "min": min(each), "timed": "each step between two events on the launch stream"},
         "flop_per_frame": fpf,
@@ -290,6 +292,19 @@ def main():
                            "unit": "GB/s", "frac": pair_bytes / (pair_ms * 1e-3) / PEAK_HBM, "bytes_per_launch": pair_bytes,
                            "note": "one pass for both replicas' sgd_step and their adpsgd_mix (lr = 0 here so the weights stay put)"}
     lrn.close()
+    # ... and the one-sided form the step above uses (this learner's update + the average with the neighbour as it stands)
+    for it in range(3):
+        bl.sgd_mix_pair(lrn.theta, nb_theta, lrn.shadow, nb_shadow, lrn.grad, None, lrn.n, 0.0)
+    ev[0].record()
+    for it in range(20):
+        bl.sgd_mix_pair(lrn.theta, nb_theta, lrn.shadow, nb_shadow, lrn.grad, None, lrn.n, 0.0)
+    ev[1].record()
+    torch.cuda.synchronize()
+    one_ms = ev[0].elapsed_time(ev[1]) / 20
+    one_bytes = lrn.n * (20 + (4 if bf else 0))
+    out["sgd_mix_one_sided"] = {"ms": one_ms, "bound": "hbm", "achieved": one_bytes / (one_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9,
+                                "unit": "GB/s", "frac": one_bytes / (one_ms * 1e-3) / PEAK_HBM, "bytes_per_launch": one_bytes,
+                                "note": "the update-and-average pass of the timed step (lr = 0 here)"}
     del lrn, nb_theta, nb_shadow, nb_grad, masters, shadows
     torch.cuda.empty_cache()
 
@@ -307,8 +322,7 @@ def main():
 
             def ostep():
                 ol.calgrad()
-                ol.apply(ow.lr)
-                bl.adpsgd_mix([ol.theta, onb], [ol.shadow, onbs], ol.n, 2, [1, 0])
+                bl.sgd_mix_pair(ol.theta, onb, ol.shadow, onbs, ol.grad, None, ol.n, ow.lr, ol.momentum, ol.velocity, None)
                 ol.weights_changed()
 
             for _ in range(3):

@@ -125,7 +125,10 @@ int adpsgd_mix(float* const* theta_master, void* const* theta_bf16_or_null, size
    theta_j' = theta_j - lr grad_j (momentum as in sgd_step, each replica with its own velocity), then both
    replicas become (theta_i' + theta_j')/2.  Same arithmetic, element by element, as sgd_step on each
    replica followed by adpsgd_mix on the pair; the weights are read and written once instead of twice.
-   All pointers are device pointers, 16-byte aligned, n elements; the bf16 copies are both given or both NULL. */
+   All pointers are device pointers, 16-byte aligned, n elements; the bf16 copies are both given or both NULL.
+   grad_j == NULL: replica j takes no update in this call (the learner that owns it has applied its own, Eq. 4's
+   first factor) and enters the average as it stands; velocity_j is then ignored.  This is one learner's
+   sgd_step followed by its adpsgd_mix with a neighbour, in one pass. */
 int sgd_mix_pair(float* theta_i, float* theta_j, void* theta_bf16_i_or_null, void* theta_bf16_j_or_null,
                  const float* grad_i, const float* grad_j, size_t n, float lr, float momentum,
                  float* velocity_i_or_null, float* velocity_j_or_null, void* stream);

@@ -692,13 +692,14 @@ int adpsgd_mix(float* const* theta, void* const* shadow, size_t n, int R, const 
 
 int sgd_mix_pair(float* theta_i, float* theta_j, void* shadow_i, void* shadow_j, const float* grad_i, const float* grad_j,
                  size_t n, float lr, float momentum, float* velocity_i, float* velocity_j, void* stream) {
-    if (!theta_i || !theta_j || !grad_i || !grad_j) return fail(BLSTM_ERR_NULL, "sgd_mix_pair: null argument");
+    // grad_j == NULL: replica j is averaged as it stands (no update, no velocity of its own here)
+    if (!theta_i || !theta_j || !grad_i) return fail(BLSTM_ERR_NULL, "sgd_mix_pair: null argument");
     if ((shadow_i == nullptr) != (shadow_j == nullptr)) return fail(BLSTM_ERR_NULL, "sgd_mix_pair: give both bf16 copies or neither");
-    if (momentum != 0.0f && (!velocity_i || !velocity_j)) return fail(BLSTM_ERR_NULL, "sgd_mix_pair: momentum needs both velocity buffers");
+    if (momentum != 0.0f && (!velocity_i || (grad_j && !velocity_j))) return fail(BLSTM_ERR_NULL, "sgd_mix_pair: momentum needs a velocity buffer for every replica that has a gradient");
     if (theta_i == theta_j) return fail(BLSTM_ERR_DIM, "sgd_mix_pair: the two replicas share a buffer");
-    if (!aligned16(theta_i) || !aligned16(theta_j) || !aligned16(grad_i) || !aligned16(grad_j) ||
+    if (!aligned16(theta_i) || !aligned16(theta_j) || !aligned16(grad_i) || (grad_j && !aligned16(grad_j)) ||
         (shadow_i && (!aligned16(shadow_i) || !aligned16(shadow_j))) ||
-        (momentum != 0.0f && (!aligned16(velocity_i) || !aligned16(velocity_j))))
+        (momentum != 0.0f && (!aligned16(velocity_i) || (grad_j && !aligned16(velocity_j)))))
         return fail(BLSTM_ERR_ALIGN, "sgd_mix_pair: pointers must be 16-byte aligned");
     return check_hip(launch_sgd_mix_pair(theta_i, theta_j, grad_i, grad_j, velocity_i, velocity_j,
                                          static_cast<unsigned short*>(shadow_i), static_cast<unsigned short*>(shadow_j),

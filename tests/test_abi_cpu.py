@@ -166,6 +166,9 @@ def test_pair_and_average_validation():
     assert L.sgd_mix_pair(a, a, None, None, ga, gb, 16, 0.1, 0.0, None, None, None) == -2
     assert L.sgd_mix_pair(a, b + 4, None, None, ga, gb, 16, 0.1, 0.0, None, None, None) == -4
     assert L.sgd_mix_pair(a, b, None, None, ga, gb, 0, 0.1, 0.0, None, None, None) == 0         # n == 0: nothing to do
+    assert L.sgd_mix_pair(a, b, None, None, ga, None, 0, 0.1, 0.0, None, None, None) == 0       # no gradient for replica j: allowed
+    assert L.sgd_mix_pair(a, b, None, None, ga, None, 0, 0.1, 0.9, 24576, None, None) == 0      # ... and then no velocity for it either
+    assert L.sgd_mix_pair(a, b, None, None, None, gb, 16, 0.1, 0.0, None, None, None) == -1     # replica i always has one
     ptrs = (ctypes.c_void_p * 4)(4096, 8192, 12288, 16384)
     assert L.sync_average(None, None, 16, 4, None) == -1
     assert L.sync_average(ptrs, None, 16, 0, None) == -2

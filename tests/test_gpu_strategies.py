@@ -27,6 +27,38 @@ def rel_err(a, ref):
 
 @pytest.mark.parametrize("n", [1, 3, 6, 1027, 4099, 1 << 20])
 @pytest.mark.parametrize("momentum", [0.0, 0.9])
+def test_one_sided_pair_update_against_oracle_and_the_two_call_form(n, momentum):
+    """sgd_mix_pair without a gradient for replica j: one learner's Eq. 1c followed by Eq. 4's average with a
+    neighbour that is taken as it stands (the oracle's pair update with a zero gradient for the neighbour)."""
+    import torch
+    from paper_1904_04956_amd import binding as bl
+    rng = np.random.default_rng(11 * n + 3)
+    a, b, ga, va = (rng.standard_normal(n).astype(np.float32) for _ in range(4))
+    lr = 0.05
+    d = {k: torch.from_numpy(v).cuda() for k, v in dict(a=a, b=b, ga=ga, va=va).items()}
+    sa = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    sb = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    e = {k: v.clone() for k, v in d.items()}
+    bl.sgd_step(e["a"], None, e["ga"], n, lr, momentum, e["va"] if momentum else None)
+    bl.adpsgd_mix([e["a"], e["b"]], None, n, 2, [1, 0])
+    bl.sgd_mix_pair(d["a"], d["b"], sa, sb, d["ga"], None, n, lr, momentum, d["va"] if momentum else None, None)
+    zero = np.zeros(n, dtype=np.float32)
+    ref, rva, _ = orc.sgd_mix_pair(a, b, ga, zero, lr, momentum, va, zero)
+    out = d["a"].cpu().numpy()
+    assert torch.equal(d["a"], d["b"])
+    assert np.abs(out - ref).max() <= 1e-6 * max(1.0, np.abs(ref).max())
+    assert torch.equal(d["a"], e["a"]) and torch.equal(d["b"], e["b"])  # same arithmetic as sgd_step + adpsgd_mix
+    if momentum:
+        assert np.abs(d["va"].cpu().numpy() - rva).max() <= 2e-7 * np.abs(rva).max()
+        assert torch.equal(d["va"], e["va"])
+    else:
+        assert np.array_equal(d["va"].cpu().numpy(), va)
+    assert np.array_equal(sa.float().cpu().numpy(), inputs.round_to_bf16(out))
+    assert torch.equal(sa, sb)
+
+
+@pytest.mark.parametrize("n", [1, 3, 6, 1027, 4099, 1 << 20])
+@pytest.mark.parametrize("momentum", [0.0, 0.9])
 def test_fused_pair_update_against_oracle_and_the_two_call_form(n, momentum):
     import torch
     from paper_1904_04956_amd import binding as bl
