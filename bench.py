@@ -76,8 +76,11 @@ def measured_traffic(workload, batch):
     return out if (ok_src and ok_batch) else {}
 
 
-def flops_by_class(T, B, D, H, L, P, V):
-    """Algorithmic FLOP of one step per kernel class (2 FLOP per multiply-add)."""
+def flops_by_class(T, B, D, H, L, P, V, softmax_wgrad_deferred=False):
+    """Algorithmic FLOP of one step per kernel class (2 FLOP per multiply-add).
+
+    softmax_wgrad_deferred: dW_s runs in the backward pass's grouped weight-gradient launch
+    (BLSTM_OPT_DEFER_SOFTMAX_WGRAD) instead of in softmax_xent_fwd_bwd."""
     M = T * B
     Z = P if P > 0 else 2 * H
     din = [D] + [2 * H] * (L - 1)
@@ -93,6 +96,9 @@ def flops_by_class(T, B, D, H, L, P, V):
     f["recurrent_bwd_persistent"] = f["gemm_recurrent_bwd"]
     f["gemm_wgrad"] = sum(2 * M * 8 * H * d for d in din) + L * 2 * (T - 1) * B * 8 * H * H + 2 * M * P * 2 * H
     f["gemm_dgrad"] = sum(2 * M * 8 * H * d for d in din[1:]) + 2 * M * 2 * H * P
+    if softmax_wgrad_deferred:
+        f["gemm_softmax_bwd"] -= 2 * M * V * Z
+        f["gemm_wgrad"] += 2 * M * V * Z
     return f
 
 
@@ -211,7 +217,7 @@ def main():
         torch.cuda.synchronize()
         prof = bl.blstm_profile_read(lrn.ctx)
         bl.blstm_profile_enable(lrn.ctx, 0)
-        fl = flops_by_class(T, B, d["D"], d["H"], d["L"], d["P"], d["V"])
+        fl = flops_by_class(T, B, d["D"], d["H"], d["L"], d["P"], d["V"], softmax_wgrad_deferred=lrn.defer_softmax_wgrad)
         classes = {}
         for name, (ms, cnt) in prof.items():
             if cnt == 0:

@@ -169,6 +169,13 @@ int adpsgd_ring_partner(int R, int64_t step, int32_t* partner_out);
    persistent kernels itself, as if one of their waits had been abandoned: every later wait returns at once, all
    kernels run to their end, everything they write is NaN, and blstm_device_status reports BLSTM_ERR_HIP. */
 #define BLSTM_OPT_TEST_ABORT 4
+/* BLSTM_OPT_DEFER_SOFTMAX_WGRAD (default 0): 1 = softmax_xent_fwd_bwd still writes the loss and dz but leaves the W_s
+   and b_s slices of grad to the next blstm_backward on this ctx, which computes them together with the other weight
+   gradients in its one grouped launch (one by one these products leave part of the device idle).  Until that call, z
+   and the workspace must stay as softmax_xent_fwd_bwd left them, and blstm_backward must be given the same grad
+   (BLSTM_ERR_DIM otherwise).  A blstm_forward in between drops what was left over.  Same arithmetic, same results.
+   softmax_xent_fwd_bwd_noalloc ignores the option. */
+#define BLSTM_OPT_DEFER_SOFTMAX_WGRAD 5
 int blstm_set_option(blstm_ctx* ctx, int option, int value);
 /* The weights behind theta have changed (see BLSTM_OPT_KEEP_WEIGHT_COPIES).  Host-side only, no device work. */
 int blstm_weights_changed(blstm_ctx* ctx);

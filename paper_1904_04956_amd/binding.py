@@ -228,6 +228,7 @@ BLSTM_OPT_RECURRENT_PATH = 1
 BLSTM_OPT_RECURRENT_SYNC = 2
 BLSTM_OPT_KEEP_WEIGHT_COPIES = 3
 BLSTM_OPT_TEST_ABORT = 4
+BLSTM_OPT_DEFER_SOFTMAX_WGRAD = 5
 BLSTM_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 

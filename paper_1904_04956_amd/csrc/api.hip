@@ -69,6 +69,9 @@ struct blstm_ctx {
     bool dax_filled;          // the forward pass's persistent kernels have marked every exchange copy of dE/da "not written yet"
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
     bool test_abort;          // failure-handling tests: the next forward pass raises the abort word itself
+    bool defer_ws;            // softmax_xent_fwd_bwd leaves dW_s and db_s to the next blstm_backward's grouped launch
+    const void* pend_z;       // ... and has done so: the z it was given (null: nothing pending) and the gradient vector
+    float* pend_grad;
     bool keep_copies;         // the caller reports weight changes (blstm_weights_changed): derived copies are kept across steps
     const void* wxp_of;       // the weights the padded W_x of layer 0 was made from (null: to be made), likewise the transposed U_h
     const void* uht_of;
@@ -132,8 +135,19 @@ inline char* at(void* base, size_t elems, size_t esz) { return static_cast<char*
 // one loss term per frame, and the float partial tiles of products split along K.
 struct SoftmaxScratch { char* logits; float* row_loss; float* partial; size_t partial_bytes; };
 
+// dW_s = du^T z with db_s as the row sums of du^T (du [M][V] in the storage type, left by the row kernel).
+GemmDesc softmax_wgrad_desc(const blstm_ctx* ctx, const char* U, const void* z, float* grad) {
+    GemmDesc d = gemm_desc(ctx, ctx->st, DT_F32);
+    d.M = ctx->V; d.N = ctx->zdim; d.atrans = true; d.btrans = true;
+    d.seg[0] = GemmSeg{U, z, ctx->V, ctx->zdim, 0, 0, ctx->M};
+    d.C = grad + ctx->off_ws; d.ldc = ctx->zdim;
+    d.rowsum = grad + ctx->off_bs;                     // db_s = sum over frames of du
+    return d;
+}
+
+// defer: the W_s and b_s slices of grad are left to the next blstm_backward (the product joins its grouped launch).
 int softmax_xent_run(blstm_ctx* ctx, const SoftmaxScratch& sc, const void* theta, const void* z, const int32_t* labels,
-                     float* loss_dev, void* dz, float* grad, hipStream_t st) {
+                     float* loss_dev, void* dz, float* grad, hipStream_t st, bool defer) {
     const int M = ctx->M, V = ctx->V, Z = ctx->zdim;
     const size_t e = ctx->esz;
     const DType S = ctx->st;
@@ -160,12 +174,11 @@ int softmax_xent_run(blstm_ctx* ctx, const SoftmaxScratch& sc, const void* theta
         d.C = dz; d.ldc = Z;
         RUN(PC_GEMM_SOFTMAX_BWD, "dz", launch_gemm(d, st));
     }
+    if (defer) { ctx->pend_z = z; ctx->pend_grad = grad; return BLSTM_OK; }
+    ctx->pend_z = nullptr;
     {   // dW_s = du^T z
-        GemmDesc d = desc(S, DT_F32);
-        d.M = V; d.N = Z; d.atrans = true; d.btrans = true;
-        d.seg[0] = GemmSeg{U, z, V, Z, 0, 0, M};
-        d.C = grad + ctx->off_ws; d.ldc = Z;
-        d.rowsum = grad + ctx->off_bs;                 // db_s = sum over frames of du
+        GemmDesc d = softmax_wgrad_desc(ctx, U, z, grad);
+        d.partial = sc.partial; d.partial_bytes = sc.partial_bytes;
         RUN(PC_GEMM_SOFTMAX_BWD, "dW_s", launch_gemm(d, st));
     }
     return BLSTM_OK;
@@ -300,6 +313,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
         w += c->part_bytes;
     }
     c->keep_copies = false; c->wxp_of = nullptr; c->uht_of = nullptr;
+    c->defer_ws = false; c->pend_z = nullptr; c->pend_grad = nullptr;
     c->ws_bytes = w;
     c->ws = nullptr; c->ws_bound = 0; c->have_forward = false;
     c->prof = false; c->recs_used = 0;
@@ -361,6 +375,7 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
     float* PRE = reinterpret_cast<float*>(ctx->ws + ctx->wPRE);
     ctx->have_forward = false;
     ctx->dax_filled = false;
+    ctx->pend_z = nullptr;                              // (a softmax weight gradient left over from an earlier step is dropped)
     const bool persistent = ctx->rec_nbg > 0 && ctx->rec_path == 0;
     if (persistent && ctx->rec_sync == 1)    // h of every layer starts as "not written yet"
         RUN(PC_MISC, "sentinel fill of h", launch_fill_bytes16(ctx->ws + ctx->wHX, ctx->hx_bytes * ctx->L, 0xFFFFFFFFu, st));
@@ -476,7 +491,7 @@ int softmax_xent_fwd_bwd(blstm_ctx* ctx, const void* theta, const void* z, const
         return fail(BLSTM_ERR_ALIGN, "softmax_xent_fwd_bwd: pointers must be 16-byte aligned");
     SoftmaxScratch sc{ctx->ws + ctx->wLOGITS, reinterpret_cast<float*>(ctx->ws + ctx->wROWLOSS),
                       reinterpret_cast<float*>(ctx->ws + ctx->wPART), ctx->part_bytes};
-    return softmax_xent_run(ctx, sc, theta, z, labels, loss_dev, dz, grad, static_cast<hipStream_t>(stream));
+    return softmax_xent_run(ctx, sc, theta, z, labels, loss_dev, dz, grad, static_cast<hipStream_t>(stream), ctx->defer_ws);
 }
 
 int softmax_xent_fwd_bwd_noalloc(blstm_ctx* ctx, const void* theta, const void* z, const int32_t* labels,
@@ -498,7 +513,7 @@ int softmax_xent_fwd_bwd_noalloc(blstm_ctx* ctx, const void* theta, const void* 
     if (rc != BLSTM_OK) return rc;
     SoftmaxScratch sc{base, reinterpret_cast<float*>(base + logits), reinterpret_cast<float*>(base + logits + rows),
                       BLSTM_NOALLOC_SCRATCH_BYTES - logits - rows};
-    return softmax_xent_run(ctx, sc, theta, z, labels, loss_dev, dz, grad, static_cast<hipStream_t>(stream));
+    return softmax_xent_run(ctx, sc, theta, z, labels, loss_dev, dz, grad, static_cast<hipStream_t>(stream), false);
 }
 
 int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void* dz, float* grad, void* stream) {
@@ -507,6 +522,8 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
     if (!ctx->have_forward) return fail(BLSTM_ERR_WORKSPACE, "blstm_backward: no forward pass is held in the workspace");
     if (!aligned16(theta) || !aligned16(x) || !aligned16(dz) || !aligned16(grad))
         return fail(BLSTM_ERR_ALIGN, "blstm_backward: pointers must be 16-byte aligned");
+    if (ctx->pend_z && ctx->pend_grad != grad)
+        return fail(BLSTM_ERR_DIM, "blstm_backward: the softmax layer's weight gradient was left to this call for another gradient vector");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int T = ctx->T, B = ctx->B, H = ctx->H, M = ctx->M, P = ctx->P;
     const size_t e = ctx->esz;
@@ -519,7 +536,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
     // a second stream beside the next layer's recurrence was measured and dropped: sharing the CUs slows the
     // recurrence, a chain of latencies, by more than the products gain.)
     std::vector<GemmDesc> wgrads;
-    wgrads.reserve(2 * ctx->L + 1);
+    wgrads.reserve(2 * ctx->L + 2);
     bool persistent = false;                            // some layer's forward pass ran the persistent kernel
     for (int l = 0; l < ctx->L; ++l) persistent = persistent || ctx->fwd_persistent[l] != 0;
     const bool sentinel = persistent && ctx->rec_sync == 1;
@@ -654,6 +671,14 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
             next_buf ^= 1;
         }
     }
+    if (ctx->pend_z) {
+        // the softmax layer's weight gradient, left to this call: dE/du still lies in the workspace.  It joins the
+        // grouped launch when it can run there (else the whole group would run product by product).
+        const GemmDesc d = softmax_wgrad_desc(ctx, ctx->ws + ctx->wLOGITS, ctx->pend_z, grad);
+        ctx->pend_z = nullptr;
+        if (gemm_group_ok(&d, 1)) wgrads.push_back(d);
+        else RUN(PC_GEMM_SOFTMAX_BWD, "dW_s", launch_gemm(d, st));
+    }
     RUN(PC_GEMM_WGRAD, "weight gradients", launch_gemm_group(wgrads.data(), (int)wgrads.size(), st));
     return BLSTM_OK;
 }
@@ -762,6 +787,11 @@ int blstm_set_option(blstm_ctx* c, int option, int value) {
         return BLSTM_OK;
     }
     if (option == BLSTM_OPT_TEST_ABORT && (value == 0 || value == 1)) { c->test_abort = value != 0; return BLSTM_OK; }
+    if (option == BLSTM_OPT_DEFER_SOFTMAX_WGRAD && (value == 0 || value == 1)) {
+        c->defer_ws = value != 0;
+        if (!c->defer_ws) c->pend_z = nullptr;
+        return BLSTM_OK;
+    }
     return fail(BLSTM_ERR_DIM, "blstm_set_option: unknown option %d or value %d", option, value);
 }
 

@@ -91,7 +91,9 @@ __device__ __forceinline__ void st_coh_8B(bf16_t* p, const uint2& v) {
 typedef unsigned int u32x4s_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void st_coh_16B(bf16_t* p, const uint4& v) {
     const u32x4s_t w = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(w) : "memory");
+    // (s_nop: a store of more than 8 bytes reads its data registers over several cycles, and a vector-ALU write to them
+    // must not follow at once; the compiler inserts that wait state for stores it knows, but cannot see into this one)
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" :: "v"(p), "v"(w) : "memory");
 }
 __device__ __forceinline__ uint4 ld_coh_16B(const bf16_t* p) {
     const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);

@@ -16,7 +16,8 @@ from . import inputs
 class Learner:
     """Buffers of one learner: master weights, bf16 shadow, gradient, batch, workspace."""
 
-    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0, recurrent_path=0, recurrent_sync=None, keep_weight_copies=True):
+    def __init__(self, T, B, D, H, L, P, V, mode, loss_scale=0.0, device="cuda:0", momentum=0.0, recurrent_path=0, recurrent_sync=None, keep_weight_copies=True,
+                 defer_softmax_wgrad=True):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the HIP path has no CPU fallback")
         self.dims = dict(T=T, B=B, D=D, H=H, L=L, P=P, V=V)
@@ -30,6 +31,10 @@ class Learner:
         bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_KEEP_WEIGHT_COPIES, int(bool(keep_weight_copies)))
         if recurrent_sync is not None:
             bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_RECURRENT_SYNC, recurrent_sync)
+        # calgrad() always runs softmax_xent_fwd_bwd and blstm_backward back to back on the same gradient vector, so the
+        # softmax layer's weight gradient may join the backward pass's grouped launch
+        bl.blstm_set_option(self.ctx, bl.BLSTM_OPT_DEFER_SOFTMAX_WGRAD, int(bool(defer_softmax_wgrad)))
+        self.defer_softmax_wgrad = bool(defer_softmax_wgrad)
         self.n = bl.blstm_param_count(self.ctx)
         self.zdim = P if P > 0 else 2 * H
         self.act_dtype = torch.bfloat16 if mode == 1 else torch.float32

@@ -196,6 +196,11 @@ def test_bench_flop_counts_match_the_closed_forms():
     per_frame = bench.flop_per_frame(260, 512, 4, 256, 32000)
     missing = 2 * 3 * (2 * 4 * 512 * 512) * 4 * B          # the frame the recurrent products skip, all three passes, four layers
     assert total == per_frame * T * B - missing
+    # with the softmax layer's weight gradient in the backward pass's grouped launch one product changes class
+    fd = bench.flops_by_class(T, B, 260, 512, 4, 256, 32000, softmax_wgrad_deferred=True)
+    moved = 2 * T * B * 32000 * 256
+    assert fd["gemm_softmax_bwd"] == f["gemm_softmax_bwd"] - moved and fd["gemm_wgrad"] == f["gemm_wgrad"] + moved
+    assert all(fd[k] == f[k] for k in f if k not in ("gemm_softmax_bwd", "gemm_wgrad"))
 
 
 def test_bench_traffic_file_is_keyed_to_the_kernel_sources(tmp_path, monkeypatch):

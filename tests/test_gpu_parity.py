@@ -43,13 +43,13 @@ def make_problem(dims, mode, seed, theta_scale=1.0):
 
 
 def check_step(dims, mode, seed, lr=0.1, theta_scale=1.0, tol=None, check_update=True, recurrent_path=0,
-               recurrent_sync=None):
+               recurrent_sync=None, defer_softmax_wgrad=True):
     """One full training step on the GPU against the oracle; returns the worst relative error."""
     from paper_1904_04956_amd.harness import Learner
     tol = TOL[mode] if tol is None else tol
     dm, theta, x, labels = make_problem(dims, mode, seed, theta_scale)
     say(f"case dims={dims} mode={mode} seed={seed}")
-    lrn = Learner(mode=mode, recurrent_path=recurrent_path, recurrent_sync=recurrent_sync, **dims)
+    lrn = Learner(mode=mode, recurrent_path=recurrent_path, recurrent_sync=recurrent_sync, defer_softmax_wgrad=defer_softmax_wgrad, **dims)
     try:
         lrn.set_theta(theta)
         lrn.set_batch(x, labels)
@@ -145,6 +145,47 @@ def test_softmax_row_widths_bf16(V):
     # one softmax row kernel per range of V (256, 512, 1024 threads per row; rows too long or too
     # ragged for the register-resident forms take the three-pass kernel)
     check_step(dict(T=2, B=5, D=8, H=8, L=1, P=8, V=V), 1, seed=80, theta_scale=4.0)
+
+
+@pytest.mark.parametrize("defer", [False, True])
+@pytest.mark.parametrize("dims", [
+    dict(T=4, B=64, D=128, H=128, L=2, P=128, V=512),       # whole 256x128 tiles everywhere: dW_s can join the grouped launch
+    dict(T=4, B=64, D=40, H=128, L=1, P=128, V=500),        # V not a whole number of tiles: dW_s runs on its own, in the backward pass
+])
+def test_softmax_weight_gradient_left_to_the_backward_pass(dims, defer):
+    # BLSTM_OPT_DEFER_SOFTMAX_WGRAD: dW_s and db_s come out of blstm_backward's grouped launch; both settings against the oracle
+    check_step(dims, 1, seed=83, theta_scale=2.0, defer_softmax_wgrad=defer)
+
+
+def test_deferred_softmax_weight_gradient_call_order():
+    # the gradient vector given to blstm_backward must be the one softmax_xent_fwd_bwd left its part to; a forward pass
+    # in between drops what was left; the two settings agree to float rounding
+    import torch
+    from paper_1904_04956_amd import binding as bl
+    from paper_1904_04956_amd.harness import Learner
+    dims = dict(T=4, B=64, D=128, H=128, L=1, P=128, V=512)
+    dm, theta, x, labels = make_problem(dims, 1, 84, 2.0)
+    grads = []
+    for defer in (False, True):
+        lrn = Learner(mode=1, defer_softmax_wgrad=defer, **dims)
+        lrn.set_theta(theta); lrn.set_batch(x, labels)
+        lrn.calgrad(); lrn.check_status()
+        grads.append(lrn.grad_numpy().copy())
+        if defer:
+            other = torch.zeros_like(lrn.grad)
+            bl.blstm_forward(lrn.ctx, lrn.theta_fwd, lrn.x, lrn.z)
+            bl.softmax_xent_fwd_bwd(lrn.ctx, lrn.theta_fwd, lrn.z, lrn.labels, lrn.loss, lrn.dz, lrn.grad)
+            with pytest.raises(RuntimeError):
+                bl.blstm_backward(lrn.ctx, lrn.theta_fwd, lrn.x, lrn.dz, other)
+            # a new forward pass drops the pending product: the backward pass then takes any gradient vector and leaves
+            # its W_s slice alone
+            bl.blstm_forward(lrn.ctx, lrn.theta_fwd, lrn.x, lrn.z)
+            bl.blstm_backward(lrn.ctx, lrn.theta_fwd, lrn.x, lrn.dz, other)
+            torch.cuda.synchronize()
+            off, k = next((o, int(np.prod(sh))) for name, o, sh in orc.layout(dm) if name == "Ws")
+            assert float(other[off:off + k].abs().max()) == 0.0
+        lrn.close()
+    assert rel_err(grads[1], grads[0]) <= 1e-5
 
 
 @pytest.mark.parametrize("dims", [

@@ -28,7 +28,7 @@ def _run_both(dims, mode, seed):
         z = inputs.round_to_bf16(z)
     labels = rng.integers(0, dm.V, size=(dm.T, dm.B)).astype(np.int32)
     print(f"case dims={dims} mode={mode} seed={seed}", flush=True)
-    lrn = Learner(mode=mode, **dims)
+    lrn = Learner(mode=mode, defer_softmax_wgrad=False, **dims)     # (softmax_xent_fwd_bwd is called on its own here: it writes dW_s itself)
     try:
         lrn.set_theta(theta)
         lrn.z.copy_(torch.from_numpy(z).to(lrn.act_dtype))
