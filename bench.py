@@ -310,6 +310,7 @@ def main():
     one_bytes = lrn.n * (20 + (4 if bf else 0))
     out["sgd_mix_one_sided"] = {"ms": one_ms, "bound": "hbm", "achieved": one_bytes / (one_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9,
                                 "unit": "GB/s", "frac": one_bytes / (one_ms * 1e-3) / PEAK_HBM, "bytes_per_launch": one_bytes,
+                                "traffic": traffic.get("sgd_mix_one_sided"),
                                 "note": "the update-and-average pass of the timed step (lr = 0 here)"}
     del lrn, nb_theta, nb_shadow, nb_grad, masters, shadows
     torch.cuda.empty_cache()
