@@ -11,7 +11,8 @@ Prints ONE JSON line:
   step_ms          median and minimum of the K steps timed one by one with events on the launch stream;
   kernel_classes   per-class durations from HIP events the library records on the launch stream;
   roofline         the kernel that takes the largest share of the step, by kernel name, against the
-                   bf16 MFMA peak; roofline_gemm: the plain product class with the largest share;
+                   bf16 MFMA peak; roofline_gemm: the product class with the largest share; roofline_recurrent:
+                   the slower of the two persistent recurrent kernels;
   adpsgd_mix ...   the streaming kernels against HBM bandwidth;
   other_workloads  the same step on the large-batch, 6x1024 and 6x512 workloads, briefly (8 timed steps each);
   cpu_baseline     the float64 oracle timed on this machine's host cores on the same workload.
@@ -245,6 +246,10 @@ def main():
         gemm = {k: v for k, v in with_flop.items() if k.startswith("gemm_")}
         if gemm:
             out["roofline_gemm"] = roofline_of(max(gemm, key=lambda k: gemm[k]["ms_per_step"]))
+        # the persistent recurrent kernels (latency chains): the slower of the two, whichever kernel leads the step
+        rec = {k: v for k, v in with_flop.items() if k.startswith("recurrent_")}
+        if rec:
+            out["roofline_recurrent"] = roofline_of(max(rec, key=lambda k: rec[k]["ms_per_step"]))
 
     # ---- the averaging kernel on R replicas of this model, against HBM bandwidth ----------------
     R = args.mix_replicas
