@@ -765,12 +765,13 @@ __global__ __launch_bounds__(128 * WN, (occupancy_target<TM, TN, WN, D, NS>())) 
 // on one XCD then belong to one or two products and share their operand panels in that XCD's L2 (with every XCD
 // walking every product, each L2 fetched its own copy of every panel: 3.4 times the algorithmic bytes, and the launch
 // ran at the HBM-side bandwidth).  Tile v belongs to the product g with first[g] <= v < first[g + 1].  No split along K.
-constexpr int GROUP_MAX = 12;
+constexpr int GROUP_MAX = 14;                          // (a six-layer model: two products per layer, the bottleneck's and the softmax layer's)
 struct GroupParams {
     Params p[GROUP_MAX];
     int first[GROUP_MAX + 1];
     int n;
 };
+static_assert(sizeof(GroupParams) <= 4096, "kernel arguments are limited to 4 KB");
 template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D, int NS>
 __global__ __launch_bounds__(128 * WN, (occupancy_target<TM, TN, WN, D, NS>())) void gemm_group_kernel(GroupParams G) {
     int x = (int)blockIdx.x;

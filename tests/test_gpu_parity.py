@@ -283,7 +283,7 @@ def test_persistent_and_stepwise_paths_agree():
 
 
 def test_weight_gradients_in_more_than_one_grouped_launch():
-    # seven layers: fifteen weight-gradient products, more than one grouped launch holds; padded first layer among them
+    # seven layers: sixteen weight-gradient products with the softmax layer's, more than one grouped launch holds (14); padded first layer among them
     check_step(dict(T=4, B=32, D=130, H=128, L=7, P=128, V=256), 1, seed=84, theta_scale=2.0)
     # shapes the 256x128 tile takes (4H = 2048, M = 256) and a layer count that fills one grouped launch exactly
     check_step(dict(T=8, B=32, D=128, H=512, L=1, P=128, V=384), 1, seed=85, theta_scale=2.0)
