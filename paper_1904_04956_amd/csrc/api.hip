@@ -360,6 +360,7 @@ int blstm_bind(blstm_ctx* c, void* workspace, size_t bytes) {
     c->have_forward = false;
     c->abort_clean = false;
     c->wxp_of = nullptr; c->uht_of = nullptr;
+    c->pend_z = nullptr;
     return BLSTM_OK;
 }
 

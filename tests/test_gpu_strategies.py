@@ -235,3 +235,13 @@ def test_paper_model_pair_update_full_size():
     ref, _, _ = orc.sgd_mix_pair(*before, 0.1)
     assert np.abs(a[idx].cpu().numpy() - ref).max() <= 1e-7
     assert torch.equal(sa.float(), a.bfloat16().float()) and torch.equal(sa, sb)
+    # the one-sided form on the same vectors (replica b enters as it stands): against sgd_step on a + adpsgd_mix, and the oracle
+    a2, b2 = ea.clone(), eb.clone()                      # (any two distinct vectors do: the pair above after its update)
+    e2a, e2b = a2.clone(), b2.clone()
+    before2 = [t[idx].cpu().numpy() for t in (a2, b2, ga)]
+    bl.sgd_mix_pair(a2, b2, sa, sb, ga, None, n, 0.1)
+    bl.sgd_step(e2a, None, ga, n, 0.1); bl.adpsgd_mix([e2a, e2b], None, n, 2, [1, 0])
+    assert torch.equal(a2, e2a) and torch.equal(b2, e2b) and torch.equal(a2, b2)
+    ref2, _, _ = orc.sgd_mix_pair(before2[0], before2[1], before2[2], np.zeros_like(before2[2]), 0.1)
+    assert np.abs(a2[idx].cpu().numpy() - ref2).max() <= 1e-7
+    assert torch.equal(sa.float(), a2.bfloat16().float()) and torch.equal(sa, sb)
