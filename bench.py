@@ -192,6 +192,20 @@ def main():
         a.record(); step(); b.record()
     torch.cuda.synchronize()
     each = [a.elapsed_time(b) for a, b in evs]
+    # for reference: the same step with the update and the averaging as the two separate calls (same bits, 10 B more per parameter)
+    def step_two_calls():
+        lrn.calgrad()
+        lrn.apply(w.lr)
+        bl.adpsgd_mix(masters, shadows, lrn.n, 2, [1, 0])
+        lrn.weights_changed()
+    for _ in range(2):
+        step_two_calls()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_two_calls()
+    torch.cuda.synchronize()
+    two_call_ms = 1e3 * (time.perf_counter() - t0) / args.steps
     fpf = flop_per_frame(d["D"], d["H"], d["L"], d["P"], d["V"])
     peak = PEAK_BF16_MFMA if bf else PEAK_FP32_MFMA
 
@@ -203,6 +217,7 @@ def main():
                                f"step = forward + softmax-xent + backward + sgd_step + adpsgd_mix with one neighbour replica (update and average in one pass)",
                    "global_batch": B, "seq_len": T, "lr": w.lr},
         "step_ms": {"median": statistics.median(each), "min": min(each), "timed": "each step between two events on the launch stream"},
+        "ms_per_step_two_call_form": two_call_ms,
         "flop_per_frame": fpf,
         "pct_of_mfma_peak": 100.0 * frames_per_s * fpf / peak,
         "final_loss": loss,
