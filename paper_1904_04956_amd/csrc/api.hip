@@ -67,7 +67,6 @@ struct blstm_ctx {
     int rec_path;             // 0 = persistent kernels where supported, 1 = one launch per frame
     int rec_sync;             // exchange of the persistent kernels: 0 = fenced counters, 1 = sentinel-tagged data
     bool dax_filled;          // the forward pass's persistent kernels have marked every exchange copy of dE/da "not written yet"
-    bool hx_filled;           // the last backward pass's grouped launch has marked every exchange copy of h "not written yet" for the next forward pass
     bool abort_clean;         // the abort word has been zeroed since the workspace was bound
     bool test_abort;          // failure-handling tests: the next forward pass raises the abort word itself
     bool defer_ws;            // softmax_xent_fwd_bwd leaves dW_s and db_s to the next blstm_backward's grouped launch
@@ -280,7 +279,7 @@ int blstm_create(const blstm_config* cfg, blstm_ctx** out) {
     }
     // persistent recurrent kernels: transposed U_h per layer and direction, counters, abort word
     c->rec_nbg = 0; c->rec_tiles = 0; c->rec_path = 0; c->rec_sync = 1; c->abort_clean = false; c->test_abort = false;
-    c->dax_filled = false; c->hx_filled = false;
+    c->dax_filled = false;
     c->fwd_persistent.assign(c->L, 0);
     c->wUHT = w; c->wCNT = w; c->wHX = w; c->wDAX = w; c->hx_bytes = 0; c->dax_bytes = 0;
     if (c->st == DT_BF16 && rec_waves_for(c->H, c->B) > 0) {
@@ -360,7 +359,6 @@ int blstm_bind(blstm_ctx* c, void* workspace, size_t bytes) {
     c->ws_bound = bytes;
     c->have_forward = false;
     c->abort_clean = false;
-    c->hx_filled = false;
     c->wxp_of = nullptr; c->uht_of = nullptr;
     c->pend_z = nullptr;
     return BLSTM_OK;
@@ -380,11 +378,8 @@ int blstm_forward(blstm_ctx* ctx, const void* theta, const void* x, void* z_out,
     ctx->dax_filled = false;
     ctx->pend_z = nullptr;                              // (a softmax weight gradient left over from an earlier step is dropped)
     const bool persistent = ctx->rec_nbg > 0 && ctx->rec_path == 0;
-    // h of every layer starts as "not written yet": the backward pass of the step before has seen to that on the side of its
-    // last launch (nothing touches these copies between the passes); otherwise one fill
-    if (persistent && ctx->rec_sync == 1 && !ctx->hx_filled)
+    if (persistent && ctx->rec_sync == 1)    // h of every layer starts as "not written yet"
         RUN(PC_MISC, "sentinel fill of h", launch_fill_bytes16(ctx->ws + ctx->wHX, ctx->hx_bytes * ctx->L, 0xFFFFFFFFu, st));
-    ctx->hx_filled = false;
     for (int l = 0; l < ctx->L; ++l) {
         const void* Xin = l == 0 ? x : static_cast<const void*>(ctx->ws + ctx->wY[l - 1]);
         const int Din = ctx->din(l);
@@ -685,12 +680,7 @@ int blstm_backward(blstm_ctx* ctx, const void* theta, const void* x, const void*
         if (gemm_group_ok(&d, 1)) wgrads.push_back(d);
         else RUN(PC_GEMM_SOFTMAX_BWD, "dW_s", launch_gemm(d, st));
     }
-    // (on the side: the exchange copies of h, which only the forward recurrence uses, are marked for the next step)
-    const bool mark_hx = ctx->rec_nbg > 0 && ctx->rec_path == 0 && ctx->rec_sync == 1 && ctx->hx_bytes > 0;
-    bool marked = false;
-    RUN(PC_GEMM_WGRAD, "weight gradients", launch_gemm_group(wgrads.data(), (int)wgrads.size(), st, mark_hx ? ctx->ws + ctx->wHX : nullptr,
-                                                              mark_hx ? ctx->hx_bytes * ctx->L : 0, &marked));
-    ctx->hx_filled = marked;
+    RUN(PC_GEMM_WGRAD, "weight gradients", launch_gemm_group(wgrads.data(), (int)wgrads.size(), st));
     return BLSTM_OK;
 }
 

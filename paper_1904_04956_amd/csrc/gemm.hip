@@ -770,19 +770,10 @@ struct GroupParams {
     Params p[GROUP_MAX];
     int first[GROUP_MAX + 1];
     int n;
-    uint4* fill;                                       // fill_words 16-byte words set to 0xFF bytes on the side (null: none)
-    unsigned long long fill_words;
 };
 static_assert(sizeof(GroupParams) <= 4096, "kernel arguments are limited to 4 KB");
 template <typename TI, typename TO, bool AT, bool BT, int TM, int TN, int WN, bool FAST, bool RS, int D, int NS>
 __global__ __launch_bounds__(128 * WN, (occupancy_target<TM, TN, WN, D, NS>())) void gemm_group_kernel(GroupParams G) {
-    if (G.fill) {
-        // a region the caller wants marked (the forward recurrence's exchange copies, "not written yet" for the next step):
-        // every workgroup sets its share before its tile, a few stores per thread beside a launch bound by the matrix cores
-        const unsigned long long per = (G.fill_words + gridDim.x - 1) / gridDim.x;
-        const unsigned long long b = (unsigned long long)blockIdx.x * per, e = b + per < G.fill_words ? b + per : G.fill_words;
-        for (unsigned long long i = b + threadIdx.x; i < e; i += 128 * WN) G.fill[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
-    }
     int x = (int)blockIdx.x;
     const int total8 = G.first[G.n] & ~7;
     if (x < total8) x = (x & 7) * (total8 >> 3) + (x >> 3);
@@ -1151,8 +1142,7 @@ bool gemm_group_ok(const GemmDesc* descs, int n) {
 }
 
 // Products the grouped kernel cannot take run one by one.
-hipError_t launch_gemm_group(const GemmDesc* descs, int n, hipStream_t stream, void* fill, size_t fill_bytes, bool* filled) {
-    if (filled) *filled = false;
+hipError_t launch_gemm_group(const GemmDesc* descs, int n, hipStream_t stream) {
     if (n <= 0) return hipSuccess;
     if (n == 1) return launch_gemm(descs[0], stream);
     if (!gemm_group_ok(descs, n)) {
@@ -1177,10 +1167,6 @@ hipError_t launch_gemm_group(const GemmDesc* descs, int n, hipStream_t stream, v
             total += G.p[k].ntm * G.p[k].ntn * (d.batch > 0 ? d.batch : 1);
         }
         G.first[G.n] = total;
-        if (i0 == 0 && fill && fill_bytes >= 16 && total > 0) {
-            G.fill = static_cast<uint4*>(fill); G.fill_words = fill_bytes / 16;
-            if (filled) *filled = true;
-        }
         if (all_r) {
             constexpr size_t lds = (size_t)(256 + 128) * CHUNKS * 16;
             static thread_local bool attr_set = false;

@@ -57,9 +57,6 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t stream);
 // bias, one segment) in one launch where the shapes allow it (gemm_group_ok); otherwise one launch each.  A grouped
 // launch never splits along K and uses no scratch.
 bool gemm_group_ok(const GemmDesc* d, int n);
-// fill (optional): fill_bytes / 16 16-byte words at `fill` (16-byte aligned) are set to 0xFF bytes by the grouped
-// kernel while it runs; *filled reports whether that happened (only a grouped launch does it).
-hipError_t launch_gemm_group(const GemmDesc* d, int n, hipStream_t stream, void* fill = nullptr, size_t fill_bytes = 0,
-                             bool* filled = nullptr);
+hipError_t launch_gemm_group(const GemmDesc* d, int n, hipStream_t stream);
 
 }  // namespace blstm
