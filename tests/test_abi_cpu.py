@@ -73,6 +73,21 @@ def test_create_rejects_bad_dimensions():
     L.blstm_destroy(None)
 
 
+def test_options_take_their_values_only():
+    ctx = bl.blstm_create(2, 2, 2, 2, 1, 0, 2, 0)
+    L = bl.lib()
+    try:
+        for opt in (bl.BLSTM_OPT_RECURRENT_PATH, bl.BLSTM_OPT_RECURRENT_SYNC, bl.BLSTM_OPT_KEEP_WEIGHT_COPIES,
+                    bl.BLSTM_OPT_TEST_ABORT, bl.BLSTM_OPT_DEFER_SOFTMAX_WGRAD):
+            assert L.blstm_set_option(ctx, opt, 1) == 0
+            assert L.blstm_set_option(ctx, opt, 0) == 0
+            assert L.blstm_set_option(ctx, opt, 2) == -2
+        assert L.blstm_set_option(ctx, 99, 0) == -2
+        assert L.blstm_set_option(None, bl.BLSTM_OPT_DEFER_SOFTMAX_WGRAD, 1) == -1
+    finally:
+        bl.blstm_destroy(ctx)
+
+
 def test_calls_validate_before_launching():
     ctx = bl.blstm_create(2, 2, 2, 2, 1, 0, 2, 0)
     L = bl.lib()
